@@ -1,0 +1,174 @@
+// px_sparse_apply_sgd / px_sparse_apply_adagrad: in-place update of the touched rows.
+//
+// Parallax Sec. 2.1: gradients are aggregated before they update the variable,
+// so every distinct id is updated exactly once from its aggregated row; Sec. 4.3:
+// the update of a (partition of a) sparse variable runs where the variable lives.
+// One lane group per row: 128-bit loads of the gradient row and the table row
+// (and accumulator row), the update, 128-bit stores.  Rows are taken in the order
+// perm gives, restricted to [range[0], range[1]) when a shard range is passed.
+#include "px_internal.h"
+
+namespace {
+
+struct ApplyArgs {
+    float* table;
+    float* accum;
+    const int64_t* ids;
+    const float* rows;
+    const int64_t* num_ids;
+    const int32_t* perm;
+    const int64_t* range;
+    uint32_t* flags;
+    int64_t vocab;
+    int64_t dim;
+    int64_t cap;
+    int pieces;          // row pieces per row (4 floats each when VEC, else 1)
+    float lr;
+    float eps;
+};
+
+template <bool VEC> struct Piece;
+template <> struct Piece<true> {
+    typedef float4 V;
+    enum { E = 4 };
+};
+template <> struct Piece<false> {
+    typedef float V;
+    enum { E = 1 };
+};
+
+__device__ __forceinline__ void sgd(float& w, float g, float lr) { w = w - lr * g; }
+__device__ __forceinline__ void adagrad(float& w, float& a, float g, float lr, float eps) {
+    a = a + g * g;
+    w = w - lr * g / (sqrtf(a) + eps);
+}
+
+template <bool ADAGRAD, bool VEC, int G, int C>
+__global__ __launch_bounds__(256) void k_apply(ApplyArgs p) {
+    typedef typename Piece<VEC>::V V;
+    enum { E = Piece<VEC>::E };
+    if (p.flags[0] & PXF_BAD_ID) return;             // an earlier call saw a bad id: leave the table alone
+    int64_t n = p.num_ids[0];
+    if (n < 0) n = 0;
+    if (n > p.cap) n = p.cap;
+    int64_t first = 0, last = n;
+    if (p.range) {
+        first = p.range[0];
+        last = p.range[1];
+        if (first < 0) first = 0;
+        if (last > n) last = n;
+    }
+    const int gl = threadIdx.x % G;
+    const int64_t group = (int64_t) blockIdx.x * (256 / G) + threadIdx.x / G;
+    const int64_t n_groups = (int64_t) gridDim.x * (256 / G);
+    for (int64_t j = first + group; j < last; j += n_groups) {
+        int64_t k = p.perm ? (int64_t) p.perm[j] : j;
+        if (k < 0 || k >= n) continue;
+        const int64_t id = p.ids[k];
+        if (id < 0 || id >= p.vocab) {
+            if (gl == 0) atomicOr(p.flags, (uint32_t) PXF_BAD_ID);
+            continue;
+        }
+        const V* g = (const V*) (p.rows + (size_t) k * p.dim);
+        V* w = (V*) (p.table + (size_t) id * p.dim);
+        V* a = ADAGRAD ? (V*) (p.accum + (size_t) id * p.dim) : nullptr;
+        for (int p0 = 0; p0 < p.pieces; p0 += G * C) {
+            V gv[C], wv[C], av[C];
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const int pc = p0 + c * G + gl;
+                if (pc < p.pieces) {
+                    gv[c] = g[pc];
+                    wv[c] = w[pc];
+                    if (ADAGRAD) av[c] = a[pc];
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const int pc = p0 + c * G + gl;
+                if (pc < p.pieces) {
+                    float* gf = (float*) &gv[c];
+                    float* wf = (float*) &wv[c];
+                    float* af = (float*) &av[c];
+#pragma unroll
+                    for (int x = 0; x < E; ++x) {
+                        if (ADAGRAD) adagrad(wf[x], af[x], gf[x], p.lr, p.eps);
+                        else sgd(wf[x], gf[x], p.lr);
+                    }
+                    w[pc] = wv[c];
+                    if (ADAGRAD) a[pc] = av[c];
+                }
+            }
+        }
+    }
+}
+
+template <bool ADAGRAD, bool VEC>
+void launch(const ApplyArgs& p, hipStream_t stream) {
+    auto blocks = [&](int g) {
+        int64_t b = (p.cap + (256 / g) - 1) / (256 / g);
+        if (b > 4096) b = 4096;
+        if (b < 1) b = 1;
+        return dim3((unsigned) b, 1, 1);
+    };
+    if (p.pieces <= 16) k_apply<ADAGRAD, VEC, 16, 1><<<blocks(16), 256, 0, stream>>>(p);
+    else if (p.pieces <= 32) k_apply<ADAGRAD, VEC, 32, 1><<<blocks(32), 256, 0, stream>>>(p);
+    else if (p.pieces <= 64) k_apply<ADAGRAD, VEC, 64, 1><<<blocks(64), 256, 0, stream>>>(p);
+    else if (p.pieces <= 128) k_apply<ADAGRAD, VEC, 64, 2><<<blocks(64), 256, 0, stream>>>(p);
+    else k_apply<ADAGRAD, VEC, 64, 4><<<blocks(64), 256, 0, stream>>>(p);
+}
+
+px_status apply_common(px_ctx* ctx, bool adagrad, float* table, float* accum, int64_t vocab, int64_t dim,
+                       const int64_t* ids, const float* rows, const int64_t* num_ids, int64_t cap,
+                       const int32_t* perm, const int64_t* range, float lr, float eps, hipStream_t stream) {
+    if (!ctx) return PX_ERR_INVALID_ARG;
+    if (vocab < 1 || dim < 1 || cap < 0 || cap >= (1ll << 31))
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "vocab %lld, dim %lld or cap %lld unsupported", (long long) vocab,
+                       (long long) dim, (long long) cap);
+    if (!num_ids || !table || (adagrad && !accum) || (cap > 0 && (!ids || !rows)))
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "null argument");
+    if (((uintptr_t) table) % 4 || ((uintptr_t) rows) % 4 || (adagrad && ((uintptr_t) accum) % 4))
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "float pointers misaligned");
+    if (cap == 0) return PX_OK;
+    ApplyArgs p;
+    p.table = table;
+    p.accum = accum;
+    p.ids = ids;
+    p.rows = rows;
+    p.num_ids = num_ids;
+    p.perm = perm;
+    p.range = range;
+    p.flags = ctx->d_flags;
+    p.vocab = vocab;
+    p.dim = dim;
+    p.cap = cap;
+    p.lr = lr;
+    p.eps = eps;
+    const bool vec = dim % 4 == 0 && ((uintptr_t) table) % 16 == 0 && ((uintptr_t) rows) % 16 == 0 &&
+                     (!adagrad || ((uintptr_t) accum) % 16 == 0);
+    p.pieces = (int) (vec ? dim / 4 : dim);
+    if (adagrad) {
+        if (vec) launch<true, true>(p, stream); else launch<true, false>(p, stream);
+    } else {
+        if (vec) launch<false, true>(p, stream); else launch<false, false>(p, stream);
+    }
+    return px_check_hip(ctx, hipGetLastError(), "apply launch");
+}
+
+}  // namespace
+
+extern "C" px_status px_sparse_apply_sgd(px_ctx* ctx, float* table, int64_t vocab, int64_t dim,
+                                         const int64_t* ids, const float* rows, const int64_t* num_ids,
+                                         int64_t cap, const int32_t* perm, const int64_t* range, float lr,
+                                         void* hip_stream) {
+    return apply_common(ctx, false, table, nullptr, vocab, dim, ids, rows, num_ids, cap, perm, range, lr, 0.f,
+                        (hipStream_t) hip_stream);
+}
+
+extern "C" px_status px_sparse_apply_adagrad(px_ctx* ctx, float* table, float* accum, int64_t vocab,
+                                             int64_t dim, const int64_t* ids, const float* rows,
+                                             const int64_t* num_ids, int64_t cap, const int32_t* perm,
+                                             const int64_t* range, float lr, float eps, void* hip_stream) {
+    return apply_common(ctx, true, table, accum, vocab, dim, ids, rows, num_ids, cap, perm, range, lr, eps,
+                        (hipStream_t) hip_stream);
+}

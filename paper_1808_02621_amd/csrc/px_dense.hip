@@ -1,0 +1,159 @@
+// px_dense_average: element-wise reduction of N workers' dense gradient buffers.
+//
+// Parallax Sec. 2.1: AllReduce computes the sum over the workers of their
+// gradients (Sec. 4.1: or the average); this is the reduction one GPU performs
+// on the slice it owns.  One streaming pass: each thread owns 16 bytes of every
+// input buffer (4 floats or 8 bfloat16), keeps 8 loads in flight, adds in worker
+// order and writes once.  Pure HBM streaming: N*C*es bytes in, C*4 (or C*2) out.
+#include "px_internal.h"
+
+namespace {
+
+#ifdef PX_DENSE_ACC_FLOAT
+typedef float acc_t;
+#else
+typedef double acc_t;
+#endif
+
+enum { DENSE_BATCH = 8 };
+
+__device__ __forceinline__ uint16_t to_bf16(float f) {   // round to nearest, ties to even
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t) (u >> 16);
+}
+
+template <typename TIN> struct In;
+template <> struct In<float> {
+    enum { E = 4 };
+    static __device__ __forceinline__ void add(acc_t* acc, const uint4& r) {
+        acc[0] += (acc_t) __uint_as_float(r.x);
+        acc[1] += (acc_t) __uint_as_float(r.y);
+        acc[2] += (acc_t) __uint_as_float(r.z);
+        acc[3] += (acc_t) __uint_as_float(r.w);
+    }
+    static __device__ __forceinline__ float widen(float v) { return v; }
+};
+template <> struct In<uint16_t> {
+    enum { E = 8 };
+    static __device__ __forceinline__ void add(acc_t* acc, const uint4& r) {
+        acc[0] += (acc_t) __uint_as_float(r.x << 16);
+        acc[1] += (acc_t) __uint_as_float(r.x & 0xffff0000u);
+        acc[2] += (acc_t) __uint_as_float(r.y << 16);
+        acc[3] += (acc_t) __uint_as_float(r.y & 0xffff0000u);
+        acc[4] += (acc_t) __uint_as_float(r.z << 16);
+        acc[5] += (acc_t) __uint_as_float(r.z & 0xffff0000u);
+        acc[6] += (acc_t) __uint_as_float(r.w << 16);
+        acc[7] += (acc_t) __uint_as_float(r.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ float widen(uint16_t v) { return __uint_as_float((uint32_t) v << 16); }
+};
+
+// Thread i owns piece i (16 bytes) of every buffer.
+template <typename TIN, bool OUT_BF16>
+__global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ words, int n_buffers,
+                                                   int64_t pieces, void* __restrict__ out, float scale) {
+    enum { E = In<TIN>::E };
+    const int64_t i = (int64_t) blockIdx.x * 256 + threadIdx.x;
+    if (i >= pieces) return;
+    const uint4* const* bufs = (const uint4* const*) (words + PXW_IDX_PTR);
+    acc_t acc[E];
+#pragma unroll
+    for (int x = 0; x < E; ++x) acc[x] = (acc_t) 0;
+    for (int w0 = 0; w0 < n_buffers; w0 += DENSE_BATCH) {
+        uint4 r[DENSE_BATCH];
+#pragma unroll
+        for (int j = 0; j < DENSE_BATCH; ++j)
+            if (w0 + j < n_buffers) r[j] = bufs[w0 + j][i];
+#pragma unroll
+        for (int j = 0; j < DENSE_BATCH; ++j)
+            if (w0 + j < n_buffers) In<TIN>::add(acc, r[j]);
+    }
+    float o[E];
+#pragma unroll
+    for (int x = 0; x < E; ++x) o[x] = (float) (acc[x] * (acc_t) scale);
+    if (OUT_BF16) {
+        uint16_t* dst = (uint16_t*) out + i * E;
+        if constexpr (E == 8) {
+            uint4 v;
+            v.x = to_bf16(o[0]) | ((uint32_t) to_bf16(o[1]) << 16);
+            v.y = to_bf16(o[2]) | ((uint32_t) to_bf16(o[3]) << 16);
+            v.z = to_bf16(o[4]) | ((uint32_t) to_bf16(o[5]) << 16);
+            v.w = to_bf16(o[6]) | ((uint32_t) to_bf16(o[7]) << 16);
+            *(uint4*) dst = v;
+        } else {
+            uint2 v;
+            v.x = to_bf16(o[0]) | ((uint32_t) to_bf16(o[1]) << 16);
+            v.y = to_bf16(o[2]) | ((uint32_t) to_bf16(o[3]) << 16);
+            *(uint2*) dst = v;
+        }
+    } else {
+        float4* dst = (float4*) ((float*) out + i * E);
+#pragma unroll
+        for (int x = 0; x < E; x += 4) dst[x / 4] = make_float4(o[x], o[x + 1], o[x + 2], o[x + 3]);
+    }
+}
+
+// One element per thread, for unaligned buffers and for the tail behind the last full piece.
+template <typename TIN, bool OUT_BF16>
+__global__ __launch_bounds__(256) void k_dense_scalar(const uint64_t* __restrict__ words, int n_buffers,
+                                                      int64_t first, int64_t count, void* __restrict__ out,
+                                                      float scale) {
+    const int64_t i = first + (int64_t) blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    const TIN* const* bufs = (const TIN* const*) (words + PXW_IDX_PTR);
+    acc_t acc = (acc_t) 0;
+    for (int w = 0; w < n_buffers; ++w) acc += (acc_t) In<TIN>::widen(bufs[w][i]);
+    const float o = (float) (acc * (acc_t) scale);
+    if (OUT_BF16) ((uint16_t*) out)[i] = to_bf16(o);
+    else ((float*) out)[i] = o;
+}
+
+template <typename TIN, bool OUT_BF16>
+void launch(px_ctx* ctx, int n, int64_t count, bool vec, void* out, float scale, hipStream_t stream) {
+    enum { E = In<TIN>::E };
+    int64_t done = 0;
+    if (vec) {
+        const int64_t pieces = count / E;
+        if (pieces > 0)
+            k_dense_vec<TIN, OUT_BF16><<<(unsigned) ((pieces + 255) / 256), 256, 0, stream>>>(ctx->d_words, n, pieces, out, scale);
+        done = pieces * E;
+    }
+    if (done < count)
+        k_dense_scalar<TIN, OUT_BF16><<<(unsigned) ((count - done + 255) / 256), 256, 0, stream>>>(ctx->d_words, n, done, count, out, scale);
+}
+
+}  // namespace
+
+extern "C" px_status px_dense_average(px_ctx* ctx, int n_buffers, const void* const* bufs, int64_t count,
+                                      px_dtype in_dtype, void* out, px_dtype out_dtype, float scale,
+                                      void* hip_stream) {
+    if (!ctx) return PX_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t) hip_stream;
+    if (n_buffers < 1 || n_buffers > PX_MAX_SOURCES)
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "n_buffers %d outside [1, %d]", n_buffers, (int) PX_MAX_SOURCES);
+    if ((in_dtype != PX_F32 && in_dtype != PX_BF16) || (out_dtype != PX_F32 && out_dtype != PX_BF16))
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "unknown dtype");
+    if (count < 0 || count > (1ll << 40)) return px_fail(ctx, PX_ERR_INVALID_ARG, "count %lld unsupported", (long long) count);
+    if (count == 0) return PX_OK;
+    if (!bufs || !out) return px_fail(ctx, PX_ERR_INVALID_ARG, "null argument");
+    const size_t es = in_dtype == PX_F32 ? 4 : 2, os = out_dtype == PX_F32 ? 4 : 2;
+    bool vec = ((uintptr_t) out) % 16 == 0;
+    if (((uintptr_t) out) % os) return px_fail(ctx, PX_ERR_INVALID_ARG, "out misaligned");
+    uint64_t host_words[PX_MAX_SOURCES];
+    for (int w = 0; w < n_buffers; ++w) {
+        if (!bufs[w] || ((uintptr_t) bufs[w]) % es) return px_fail(ctx, PX_ERR_INVALID_ARG, "buffer %d null or misaligned", w);
+        if (((uintptr_t) bufs[w]) % 16) vec = false;
+        host_words[w] = (uint64_t) (uintptr_t) bufs[w];
+    }
+    px_status st = px_upload_words(ctx, ctx->d_words + PXW_IDX_PTR, host_words, n_buffers, nullptr, 0, stream);
+    if (st != PX_OK) return st;
+    if (in_dtype == PX_F32) {
+        if (out_dtype == PX_F32) launch<float, false>(ctx, n_buffers, count, vec, out, scale, stream);
+        else launch<float, true>(ctx, n_buffers, count, vec, out, scale, stream);
+    } else {
+        if (out_dtype == PX_F32) launch<uint16_t, false>(ctx, n_buffers, count, vec, out, scale, stream);
+        else launch<uint16_t, true>(ctx, n_buffers, count, vec, out, scale, stream);
+    }
+    return px_check_hip(ctx, hipGetLastError(), "dense launch");
+}

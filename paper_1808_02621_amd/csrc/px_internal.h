@@ -1,0 +1,65 @@
+// Private declarations shared by the HIP sources of libpx (gfx950 only).
+#ifndef PX_INTERNAL_H_
+#define PX_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "px.h"
+
+struct px_ctx {
+    int device;
+    uint64_t* d_words;   // device: pointer / offset tables uploaded per call
+    uint32_t* d_flags;   // device: [0] sticky error flag
+    uint32_t* h_flags;   // pinned host mirror for px_device_status
+    char err[512];
+};
+
+// Layout of d_words (64-bit words).
+enum {
+    PXW_IDX_PTR = 0,                        // idx[w]   (coalesce) / bufs[w] (dense)
+    PXW_VAL_PTR = PX_MAX_SOURCES,           // val[w]
+    PXW_PREFIX = 2 * PX_MAX_SOURCES,        // row prefix, n_workers + 1 entries
+    PXW_TOTAL = 3 * PX_MAX_SOURCES + 8
+};
+
+enum { PXF_BAD_ID = 1u };                   // bits of d_flags[0]
+
+px_status px_fail(px_ctx* ctx, px_status s, const char* fmt, ...);
+px_status px_check_hip(px_ctx* ctx, hipError_t e, const char* what);
+
+// Copies `n` host words into device memory at `dst` through kernel arguments
+// (no host staging buffer, safe to capture), and zeroes `nzero` 32-bit words at `zero`.
+px_status px_upload_words(px_ctx* ctx, uint64_t* dst, const uint64_t* host_words, int n,
+                          uint32_t* zero, int nzero, hipStream_t stream);
+
+static inline size_t px_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- radix passes
+// One stable 8-bit counting pass = a histogram kernel (per block, per digit) and
+// a scatter kernel that derives its own offsets from the histogram matrix.
+enum {
+    PX_SORT_THREADS = 256,
+    PX_SORT_ITEMS = 8,
+    PX_SORT_TILE = PX_SORT_THREADS * PX_SORT_ITEMS,   // items ranked at once in LDS
+    PX_SORT_MAX_BLOCKS = 512,
+    PX_RADIX = 256
+};
+
+struct px_sort_geom {
+    int n_blocks;      // blocks of a pass
+    int64_t chunk;     // items per block, a multiple of PX_SORT_TILE
+};
+
+static inline px_sort_geom px_sort_geometry(int64_t n) {
+    px_sort_geom g;
+    int64_t per = (n + PX_SORT_MAX_BLOCKS - 1) / PX_SORT_MAX_BLOCKS;
+    g.chunk = (per + PX_SORT_TILE - 1) / PX_SORT_TILE * PX_SORT_TILE;
+    if (g.chunk < PX_SORT_TILE) g.chunk = PX_SORT_TILE;
+    g.n_blocks = (int) ((n + g.chunk - 1) / g.chunk);
+    if (g.n_blocks < 1) g.n_blocks = 1;
+    return g;
+}
+
+#endif  // PX_INTERNAL_H_

@@ -1,0 +1,86 @@
+// px_partition_rows: split the aggregated rows of a sparse variable into P disjoint shards.
+//
+// Parallax Sec. 3.2: partitioning divides incoming indices and values into
+// disjoint sets so that aggregation and update run per partition.  A shard is
+// H(id) mod P; grouping the row positions by shard is one stable counting pass
+// with the shard number as the digit, so ascending ids stay ascending inside a
+// shard.  The number of ids is a device scalar: the grid is sized for the
+// capacity and every block clamps to the real count.
+#include "px_radix.h"
+
+namespace {
+
+struct ShardPass {
+    typedef uint32_t Item;                 // position of the id in the input
+    const int64_t* ids;
+    const int64_t* num;
+    int64_t cap;
+    uint32_t n_shards;
+    int mul_hash;
+    int32_t* out_perm;
+    int32_t* out_shard;
+
+    __device__ int64_t count() const {
+        int64_t n = num[0];
+        if (n < 0) n = 0;
+        if (n > cap) n = cap;
+        return n;
+    }
+    __device__ Item load(int64_t i) const { return (uint32_t) i; }
+    __device__ uint32_t digit(Item, int64_t i) const {
+        uint64_t h = (uint64_t) ids[i];
+        if (mul_hash) h *= 2654435761ull;              // wraps modulo 2^64
+        if ((n_shards & (n_shards - 1u)) == 0u) return (uint32_t) h & (n_shards - 1u);
+        return (uint32_t) (h % (uint64_t) n_shards);
+    }
+    __device__ void note(int64_t i, uint32_t d) const {
+        if (out_shard) out_shard[i] = (int32_t) d;
+    }
+    __device__ void store(uint32_t dst, Item v) const { out_perm[dst] = (int32_t) v; }
+};
+
+// offsets[p] = number of ids in shards below p; offsets[P] = number of ids.
+__global__ __launch_bounds__(256) void k_shard_offsets(const uint32_t* __restrict__ hist, int n_blocks,
+                                                       int n_shards, int64_t* __restrict__ offsets) {
+    __shared__ uint32_t s_wave[4];
+    const int tid = threadIdx.x;
+    uint32_t total = 0;
+    for (int b = 0; b < n_blocks; ++b) total += hist[(size_t) b * PX_RADIX + tid];
+    uint32_t grand;
+    const uint32_t start = pxr::block_exclusive_scan_256(total, s_wave, &grand);
+    if (tid < n_shards) offsets[tid] = (int64_t) start;
+    if (tid == 0) offsets[n_shards] = (int64_t) grand;
+}
+
+}  // namespace
+
+extern "C" size_t px_partition_scratch_bytes(int64_t cap) {
+    if (cap < 0) return 0;
+    return px_align_up((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX * 4, 256);
+}
+
+extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids,
+                                       int64_t cap, int num_shards, px_hash hash, int32_t* out_shard,
+                                       int32_t* out_perm, int64_t* out_offsets, void* scratch,
+                                       size_t scratch_bytes, void* hip_stream) {
+    if (!ctx) return PX_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t) hip_stream;
+    if (num_shards < 1 || num_shards > PX_MAX_SHARDS)
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "num_shards %d outside [1, %d]", num_shards, (int) PX_MAX_SHARDS);
+    if (hash != PX_HASH_MOD && hash != PX_HASH_MUL) return px_fail(ctx, PX_ERR_INVALID_ARG, "unknown hash %d", (int) hash);
+    if (cap < 0 || cap >= (1ll << 31)) return px_fail(ctx, PX_ERR_INVALID_ARG, "cap %lld outside [0, 2^31)", (long long) cap);
+    if (!num_ids || !out_offsets || !scratch || (cap > 0 && (!ids || !out_perm)))
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "null argument");
+    if (((uintptr_t) scratch) % 256) return px_fail(ctx, PX_ERR_INVALID_ARG, "scratch needs 256-byte alignment");
+    const size_t need = px_partition_scratch_bytes(cap);
+    if (scratch_bytes < need) return px_fail(ctx, PX_ERR_SCRATCH_TOO_SMALL, "scratch %zu < %zu bytes", scratch_bytes, need);
+
+    uint32_t* hist = (uint32_t*) scratch;
+    const px_sort_geom g = px_sort_geometry(cap);
+    ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard};
+    pxr::k_radix_hist<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.chunk);
+    k_shard_offsets<<<1, 256, 0, stream>>>(hist, g.n_blocks, num_shards, out_offsets);
+    if (cap > 0)
+        pxr::k_radix_scatter<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.n_blocks, g.chunk);
+    return px_check_hip(ctx, hipGetLastError(), "partition launch");
+}

@@ -1,0 +1,182 @@
+// Stable 8-bit counting pass for wave64: the building block of the id sort
+// (least-significant-digit radix sort) and of the shard partition.
+//
+// A pass is two kernels and uses no atomics on global memory and no waiting
+// between workgroups:
+//   hist     block b counts the digits of its chunk       -> hist[b][256]
+//   scatter  block b sums hist over all blocks (bin totals) and over the blocks
+//            before it, scans the totals, then ranks its chunk tile by tile in
+//            LDS and writes every item to its final place.
+// Ranking inside a tile is by wave-wide digit matching (ballots), with one LDS
+// counter row per wave, so equal digits keep their input order.
+#ifndef PX_RADIX_H_
+#define PX_RADIX_H_
+
+#include "px_internal.h"
+
+namespace pxr {
+
+__device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
+
+__device__ __forceinline__ uint64_t lanes_below() {
+    uint32_t l = lane_id();
+    return l == 0 ? 0ull : (~0ull >> (64u - l));
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+    uint32_t l = lane_id();
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t t = __shfl_up(v, o);
+        if (l >= (uint32_t) o) v += t;
+    }
+    return v;
+}
+
+// Exclusive scan over the 256 threads of a block; *total gets the block sum.
+// s_wave: 4 words of LDS.  Contains two __syncthreads.
+__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* s_wave,
+                                                             uint32_t* total) {
+    uint32_t l = lane_id(), w = threadIdx.x >> 6;
+    uint32_t incl = wave_inclusive_scan(v);
+    if (l == 63) s_wave[w] = incl;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < 4; ++i) {
+        uint32_t x = s_wave[i];
+        if (i < w) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + incl - v;
+}
+
+// Policy P supplies: typedef Item; count(); load(i); digit(item, i); note(i, d); store(dst, item).
+
+template <class P>
+__global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_hist(P p, uint32_t* __restrict__ hist,
+                                                                int64_t chunk) {
+    __shared__ uint32_t s_hist[PX_RADIX];
+    const int tid = threadIdx.x;
+    s_hist[tid] = 0u;
+    __syncthreads();
+    const int64_t n = p.count();
+    const int64_t begin = (int64_t) blockIdx.x * chunk;
+    int64_t end = begin + chunk;
+    if (end > n) end = n;
+    for (int64_t i = begin + tid; i < end; i += PX_SORT_THREADS) {
+        uint32_t d = p.digit(p.load(i), i);
+        p.note(i, d);
+        atomicAdd(&s_hist[d], 1u);
+    }
+    __syncthreads();
+    hist[(size_t) blockIdx.x * PX_RADIX + tid] = s_hist[tid];
+}
+
+template <class P>
+__global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const uint32_t* __restrict__ hist,
+                                                                   int n_blocks, int64_t chunk) {
+    typedef typename P::Item Item;
+    __shared__ Item s_items[PX_SORT_TILE];
+    __shared__ uint8_t s_dig[PX_SORT_TILE];
+    __shared__ uint32_t s_wcnt[4][PX_RADIX];
+    __shared__ uint32_t s_binstart[PX_RADIX];
+    __shared__ uint32_t s_gdst[PX_RADIX];
+    __shared__ uint32_t s_wave[4];
+
+    const int tid = threadIdx.x;
+    const uint32_t lane = lane_id();
+    const int wave = tid >> 6;
+    const uint64_t below = lanes_below();
+
+    // Where bin `tid` of this block starts in the output.
+    uint32_t total = 0, before = 0;
+    for (int b = 0; b < n_blocks; ++b) {
+        uint32_t v = hist[(size_t) b * PX_RADIX + tid];
+        total += v;
+        if (b < (int) blockIdx.x) before += v;
+    }
+    uint32_t grand;
+    uint32_t gpos = block_exclusive_scan_256(total, s_wave, &grand) + before;
+
+    const int64_t n = p.count();
+    const int64_t begin = (int64_t) blockIdx.x * chunk;
+    int64_t end = begin + chunk;
+    if (end > n) end = n;
+
+    for (int64_t tile0 = begin; tile0 < end; tile0 += PX_SORT_TILE) {
+        const int tcount = (int) ((end - tile0) < PX_SORT_TILE ? (end - tile0) : PX_SORT_TILE);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) s_wcnt[w][tid] = 0u;
+        __syncthreads();
+
+        Item it[PX_SORT_ITEMS];
+        uint32_t dg[PX_SORT_ITEMS], rk[PX_SORT_ITEMS];
+#pragma unroll
+        for (int i = 0; i < PX_SORT_ITEMS; ++i) {
+            const int local = wave * (64 * PX_SORT_ITEMS) + i * 64 + (int) lane;
+            const bool valid = local < tcount;
+            Item v = Item(0);
+            uint32_t d = 0;
+            if (valid) {
+                v = p.load(tile0 + local);
+                d = p.digit(v, tile0 + local);
+            }
+            uint64_t same = __ballot(valid);
+#pragma unroll
+            for (int bit = 0; bit < 8; ++bit) {
+                const bool one = (d >> bit) & 1u;
+                const uint64_t bb = __ballot(one);
+                same &= one ? bb : ~bb;
+            }
+            const uint32_t r = (uint32_t) __popcll(same & below);
+            uint32_t old = 0;
+            if (valid && r == 0) {                 // first lane holding this digit
+                old = s_wcnt[wave][d];
+                s_wcnt[wave][d] = old + (uint32_t) __popcll(same);
+            }
+            const int leader = valid ? (__ffsll((unsigned long long) same) - 1) : (int) lane;
+            old = __shfl(old, leader);
+            it[i] = v;
+            dg[i] = d;
+            rk[i] = old + r;
+        }
+        __syncthreads();
+
+        // Per bin: exclusive prefix over the four waves, then over the bins.
+        const uint32_t c0 = s_wcnt[0][tid], c1 = s_wcnt[1][tid], c2 = s_wcnt[2][tid], c3 = s_wcnt[3][tid];
+        s_wcnt[0][tid] = 0u;
+        s_wcnt[1][tid] = c0;
+        s_wcnt[2][tid] = c0 + c1;
+        s_wcnt[3][tid] = c0 + c1 + c2;
+        const uint32_t tot = c0 + c1 + c2 + c3;
+        uint32_t tile_total;
+        const uint32_t bs = block_exclusive_scan_256(tot, s_wave, &tile_total);
+        s_binstart[tid] = bs;
+        s_gdst[tid] = gpos - bs;                   // wraps; the sum below is exact mod 2^32
+        gpos += tot;
+        __syncthreads();
+
+#pragma unroll
+        for (int i = 0; i < PX_SORT_ITEMS; ++i) {
+            const int local = wave * (64 * PX_SORT_ITEMS) + i * 64 + (int) lane;
+            if (local < tcount) {
+                const uint32_t pos = s_binstart[dg[i]] + s_wcnt[wave][dg[i]] + rk[i];
+                s_items[pos] = it[i];
+                s_dig[pos] = (uint8_t) dg[i];
+            }
+        }
+        __syncthreads();
+        for (int j = tid; j < tcount; j += PX_SORT_THREADS) {
+            const uint32_t d = s_dig[j];
+            p.store(s_gdst[d] + (uint32_t) j, s_items[j]);
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace pxr
+
+#endif  // PX_RADIX_H_

@@ -1,0 +1,95 @@
+"""Device-buffer plumbing around the px entry points: allocate, upload, call in order.
+
+Used by the tests, the smoke check and the benchmark so that all three drive the
+library the same way.  No arithmetic of the method happens here.
+"""
+
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import px
+
+
+def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
+    """numpy -> device tensor; uint16 arrays are bfloat16 bit patterns."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+@dataclasses.dataclass
+class SparseBuffers:
+    """Everything one sparse variable's coalesce -> partition -> apply chain touches on the device."""
+
+    idx: List[torch.Tensor]
+    val: List[torch.Tensor]
+    dim: int
+    vocab: int
+    total_rows: int
+    out_ids: torch.Tensor
+    out_rows: torch.Tensor
+    out_num: torch.Tensor
+    out_run_len: torch.Tensor
+    scratch: torch.Tensor
+    shard: torch.Tensor
+    perm: torch.Tensor
+    offsets: torch.Tensor
+    part_scratch: torch.Tensor
+    n_shards: int
+    hash: int
+
+
+def sparse_buffers(idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], dim: int, vocab: int,
+                   n_shards: int, hash: int, device="cuda") -> SparseBuffers:
+    m = int(sum(int(i.numel()) for i in idx))
+    cap = max(m, 1)
+    return SparseBuffers(
+        idx=list(idx), val=list(val), dim=dim, vocab=vocab, total_rows=m,
+        out_ids=torch.empty(cap, dtype=torch.int64, device=device),
+        out_rows=torch.empty((cap, dim), dtype=torch.float32, device=device),
+        out_num=torch.zeros(1, dtype=torch.int64, device=device),
+        out_run_len=torch.empty(cap, dtype=torch.int32, device=device),
+        scratch=px.alloc_scratch(px.Context.px_coalesce_scratch_bytes(m, dim), device),
+        shard=torch.empty(cap, dtype=torch.int32, device=device),
+        perm=torch.empty(cap, dtype=torch.int32, device=device),
+        offsets=torch.empty(n_shards + 1, dtype=torch.int64, device=device),
+        part_scratch=px.alloc_scratch(px.Context.px_partition_scratch_bytes(m), device),
+        n_shards=n_shards, hash=hash)
+
+
+def coalesce(ctx: px.Context, b: SparseBuffers, scale: float = 1.0, stream=None) -> None:
+    ctx.px_sparse_coalesce(b.idx, b.val, b.dim, b.vocab, scale, b.out_ids, b.out_rows, b.out_num,
+                           b.out_run_len, b.scratch, stream)
+
+
+def partition(ctx: px.Context, b: SparseBuffers, stream=None) -> None:
+    ctx.px_partition_rows(b.out_ids, b.out_num, b.total_rows, b.n_shards, b.hash, b.shard, b.perm,
+                          b.offsets, b.part_scratch, stream)
+
+
+def apply(ctx: px.Context, b: SparseBuffers, table: torch.Tensor, accum: Optional[torch.Tensor],
+          optimizer: str, lr: float, eps: float = 0.0, use_perm: bool = True,
+          range_: Optional[torch.Tensor] = None, stream=None) -> None:
+    perm = b.perm if use_perm else None
+    if optimizer == "sgd":
+        ctx.px_sparse_apply_sgd(table, b.out_ids, b.out_rows, b.out_num, b.total_rows, perm, range_, lr,
+                                stream)
+    elif optimizer == "adagrad":
+        ctx.px_sparse_apply_adagrad(table, accum, b.out_ids, b.out_rows, b.out_num, b.total_rows, perm,
+                                    range_, lr, eps, stream)
+    else:
+        raise ValueError(optimizer)
+
+
+def sparse_step(ctx: px.Context, b: SparseBuffers, table: torch.Tensor, accum: Optional[torch.Tensor],
+                optimizer: str, lr: float, scale: float = 1.0, stream=None) -> None:
+    """coalesce -> partition -> apply (all shards), enqueued back to back."""
+    coalesce(ctx, b, scale, stream)
+    partition(ctx, b, stream)
+    apply(ctx, b, table, accum, optimizer, lr, stream=stream)

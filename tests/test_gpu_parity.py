@@ -1,0 +1,448 @@
+"""HIP path against the CPU oracle, element by element, through the C ABI (needs an MI355X).
+
+Bars: ids, counts, run lengths, shard numbers, perm and offsets bit-exact;
+float32 rows / tables / accumulators within |x - ref| <= 1e-6 + 1e-5 |ref|;
+bf16-valued inputs within 1e-2 relative (they agree far more tightly, since both
+sides widen exactly and accumulate wider than float32).
+"""
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1808_02621_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+ABS_TOL, REL_TOL = 1e-6, 1e-5
+
+
+def close(x, ref, rel=REL_TOL, abs_=ABS_TOL):
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    bad = np.abs(x - ref) > abs_ + rel * np.abs(ref)
+    assert not bad.any(), "%d of %d elements off, worst |diff| %g" % (
+        int(bad.sum()), bad.size, float(np.max(np.abs(x - ref))))
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_1808_02621_amd import px, runner
+    ctx = px.Context(0)
+    yield ctx, px, runner
+    ctx.close()
+
+
+def run_chain(gpu, idx, val, dim, vocab, n_shards, hash_name, optimizer, lr, table, accum=None,
+              scale=1.0, check_rows_exact=False, rel=REL_TOL):
+    """Runs coalesce -> partition -> apply on the GPU and on the oracle and compares everything."""
+    ctx, px, runner = gpu
+    hash_code = px.PX_HASH_MUL if hash_name == "mul" else px.PX_HASH_MOD
+    d_idx = [runner.to_device(i) for i in idx]
+    d_val = [runner.to_device(v).reshape(-1, dim) for v in val]
+    b = runner.sparse_buffers(d_idx, d_val, dim, vocab, n_shards, hash_code)
+    d_table = torch.from_numpy(table).cuda()
+    d_accum = None if accum is None else torch.from_numpy(accum).cuda()
+    runner.sparse_step(ctx, b, d_table, d_accum, optimizer, lr, scale)
+    assert ctx.px_device_status() == px.PX_OK
+    u = int(b.out_num.item())
+
+    o_ids, o_rows, o_len = oracle.sparse_coalesce(idx, val, dim, vocab, average=False)
+    if scale != 1.0:
+        o_ids, o_rows, o_len = oracle.sparse_coalesce(idx, val, dim, vocab, average=True)
+    assert u == o_ids.size
+    assert np.array_equal(b.out_ids[:u].cpu().numpy(), o_ids)
+    assert np.array_equal(b.out_run_len[:u].cpu().numpy(), o_len)
+    g_rows = b.out_rows[:u].cpu().numpy()
+    if check_rows_exact:
+        assert np.array_equal(g_rows, o_rows)
+    else:
+        close(g_rows, o_rows, rel)
+
+    o_shard, o_perm, o_off = oracle.partition_rows(o_ids, n_shards, hash_name)
+    assert np.array_equal(b.shard[:u].cpu().numpy(), o_shard)
+    assert np.array_equal(b.perm[:u].cpu().numpy(), o_perm)
+    assert np.array_equal(b.offsets.cpu().numpy(), o_off)
+
+    ref_table = table.copy()
+    if optimizer == "sgd":
+        oracle.sparse_apply_sgd(ref_table, o_ids, o_rows, lr, perm=o_perm)
+    else:
+        ref_accum = accum.copy()
+        oracle.sparse_apply_adagrad(ref_table, ref_accum, o_ids, o_rows, lr, perm=o_perm)
+        g_accum = d_accum.cpu().numpy()
+        close(g_accum[o_ids], ref_accum[o_ids], rel)
+    g_table = d_table.cpu().numpy()
+    close(g_table[o_ids], ref_table[o_ids], rel)
+    untouched = np.ones(vocab, dtype=bool)
+    untouched[o_ids] = False
+    assert np.array_equal(g_table[untouched], table[untouched])
+    if accum is not None:
+        assert np.array_equal(g_accum[untouched], accum[untouched])
+    return b, u
+
+
+def run_workload(gpu, w, table_index=0, permute=False, rel=REL_TOL):
+    idx = inputs.sparse_ids(w, table_index, permute)
+    val = inputs.sparse_values(w, table_index)
+    table = inputs.table_init(w, table_index)
+    accum = inputs.accum_init(w) if w.optimizer == "adagrad" else None
+    return run_chain(gpu, idx, val, w.dim, w.vocab, w.n_shards, w.hash, w.optimizer, w.lr, table, accum,
+                     rel=rel)
+
+
+# ------------------------------------------------------------- the workloads
+
+def test_tiny(gpu):
+    run_workload(gpu, inputs.TINY)
+
+
+def test_small_lm(gpu):
+    run_workload(gpu, inputs.SMALL_LM)
+
+
+def test_small_lm_scattered_hot_ids(gpu):
+    run_workload(gpu, inputs.SMALL_LM, permute=True)
+
+
+def test_large_lm_shrunk(gpu):
+    run_workload(gpu, inputs.shrink(inputs.LARGE_LM, vocab=50_000, n_per_worker=300))
+
+
+def test_nmt_shrunk_both_tables(gpu):
+    w = inputs.shrink(inputs.NMT, n_workers=12, n_per_worker=1000)
+    run_workload(gpu, w, 0, rel=1e-2)
+    run_workload(gpu, w, 1, rel=1e-2)
+    run_workload(gpu, w, 0)        # the agreement is in fact at the float32 bar
+
+
+def test_stress_shrunk(gpu):
+    run_workload(gpu, inputs.shrink(inputs.STRESS_UNIFORM, vocab=300_000, n_workers=16, n_per_worker=4000))
+    run_workload(gpu, inputs.shrink(inputs.STRESS_ZIPF, vocab=300_000, n_workers=16, n_per_worker=4000))
+
+
+def test_large_lm_full_size(gpu):
+    run_workload(gpu, inputs.LARGE_LM)
+
+
+def test_nmt_full_size(gpu):
+    run_workload(gpu, inputs.NMT, 0)
+    run_workload(gpu, inputs.NMT, 1)
+
+
+def test_stress_full_size(gpu):
+    run_workload(gpu, inputs.STRESS_UNIFORM)
+    run_workload(gpu, inputs.STRESS_ZIPF)
+
+
+# ------------------------------------------------------------------- shapes
+
+@pytest.mark.parametrize("dim", [1, 3, 7, 8, 20, 64, 100, 132, 300, 1028, 2052])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_row_widths(gpu, dim, bf16):
+    rng = np.random.default_rng(dim * 2 + int(bf16))
+    vocab, n_workers = 500, 5
+    idx = [inputs.draw_ids(rng, vocab, 1.1, int(n)) for n in rng.integers(50, 400, size=n_workers)]
+    val = [rng.standard_normal((i.size, dim), dtype=np.float32) for i in idx]
+    if bf16:
+        val = [inputs.f32_to_bf16_bits(v) for v in val]
+    table = (rng.standard_normal((vocab, dim)) * 0.02).astype(np.float32)
+    accum = np.full((vocab, dim), 0.1, dtype=np.float32)
+    run_chain(gpu, idx, val, dim, vocab, 3, "mul", "adagrad", 0.1, table, accum)
+
+
+def test_unaligned_value_pointers(gpu):
+    """Value rows that start 4 bytes into an allocation take the element-wise path."""
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(3)
+    dim, vocab = 64, 200
+    idx = [rng.integers(0, vocab, size=300, dtype=np.int64) for _ in range(2)]
+    val = [rng.standard_normal((300, dim), dtype=np.float32) for _ in range(2)]
+    d_idx = [runner.to_device(i) for i in idx]
+    backing = [torch.empty(300 * dim + 1, dtype=torch.float32, device="cuda") for _ in range(2)]
+    d_val = []
+    for bk, v in zip(backing, val):
+        bk[1:].copy_(torch.from_numpy(v).reshape(-1))
+        d_val.append(bk[1:])
+        assert d_val[-1].data_ptr() % 16 == 4
+    b = runner.sparse_buffers(d_idx, d_val, dim, vocab, 2, px.PX_HASH_MOD)
+    runner.coalesce(ctx, b)
+    u = int(b.out_num.item())
+    o_ids, o_rows, _ = oracle.sparse_coalesce(idx, val, dim, vocab)
+    assert np.array_equal(b.out_ids[:u].cpu().numpy(), o_ids)
+    close(b.out_rows[:u].cpu().numpy(), o_rows)
+
+
+# ---------------------------------------------------------------- edge cases
+
+def test_empty_input(gpu):
+    ctx, px, runner = gpu
+    dim, vocab = 16, 100
+    e_i = torch.zeros(0, dtype=torch.int64, device="cuda")
+    e_v = torch.zeros((0, dim), dtype=torch.float32, device="cuda")
+    b = runner.sparse_buffers([e_i, e_i], [e_v, e_v], dim, vocab, 4, px.PX_HASH_MUL)
+    b.out_num.fill_(77)
+    table = torch.randn(vocab, dim, device="cuda")
+    before = table.clone()
+    runner.sparse_step(ctx, b, table, None, "sgd", 0.5)
+    assert int(b.out_num.item()) == 0
+    assert np.array_equal(b.offsets.cpu().numpy(), np.zeros(5, dtype=np.int64))
+    assert torch.equal(table, before)
+
+
+def test_ragged_workers_with_an_empty_one(gpu):
+    rng = np.random.default_rng(4)
+    dim, vocab = 32, 1000
+    sizes = [0, 1, 2047, 0, 2049, 5]
+    idx = [rng.integers(0, vocab, size=n, dtype=np.int64) for n in sizes]
+    val = [rng.standard_normal((n, dim), dtype=np.float32) for n in sizes]
+    table = np.zeros((vocab, dim), dtype=np.float32)
+    run_chain(gpu, idx, val, dim, vocab, 7, "mod", "sgd", 1.0, table)
+
+
+def test_single_worker_all_distinct_is_a_permutation(gpu):
+    rng = np.random.default_rng(5)
+    dim, vocab = 48, 6000
+    ids = rng.permutation(vocab)[:5000].astype(np.int64)
+    val = rng.standard_normal((5000, dim), dtype=np.float32)
+    table = np.zeros((vocab, dim), dtype=np.float32)
+    run_chain(gpu, [ids], [val], dim, vocab, 2, "mod", "sgd", 1.0, table, check_rows_exact=True)
+
+
+def test_all_rows_share_one_id(gpu):
+    """One run through every tile: the border-crossing path end to end."""
+    rng = np.random.default_rng(6)
+    dim, vocab = 128, 50
+    idx = [np.full(3000, 17, dtype=np.int64) for _ in range(4)]
+    val = [rng.standard_normal((3000, dim), dtype=np.float32) for _ in range(4)]
+    table = np.zeros((vocab, dim), dtype=np.float32)
+    b, u = run_chain(gpu, idx, val, dim, vocab, 4, "mul", "sgd", 0.01, table)
+    assert u == 1
+
+
+def test_integer_valued_rows_are_bit_exact(gpu):
+    rng = np.random.default_rng(7)
+    dim, vocab = 256, 300
+    idx = [inputs.draw_ids(rng, vocab, 1.3, 6000) for _ in range(6)]
+    val = [inputs.small_integer_values(rng, (6000, dim)) for _ in range(6)]
+    table = np.zeros((vocab, dim), dtype=np.float32)
+    run_chain(gpu, idx, val, dim, vocab, 8, "mul", "sgd", 1.0, table, check_rows_exact=True)
+
+
+def test_average_scale(gpu):
+    rng = np.random.default_rng(8)
+    dim, vocab, n = 64, 400, 8
+    idx = [inputs.draw_ids(rng, vocab, 1.0, 500) for _ in range(n)]
+    val = [rng.standard_normal((500, dim), dtype=np.float32) for _ in range(n)]
+    table = np.zeros((vocab, dim), dtype=np.float32)
+    run_chain(gpu, idx, val, dim, vocab, 4, "mul", "sgd", 0.1, table, scale=1.0 / n)
+
+
+def test_vocab_of_one_and_of_two_to_the_32(gpu):
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(9)
+    dim = 8
+    val = [rng.standard_normal((100, dim), dtype=np.float32)]
+    table = np.zeros((1, dim), dtype=np.float32)
+    run_chain(gpu, [np.zeros(100, dtype=np.int64)], val, dim, 1, 1, "mod", "sgd", 1.0, table)
+    # ids that need all 32 key bits (coalesce and partition only: no table that large)
+    vocab = 1 << 32
+    ids = np.concatenate([rng.integers(vocab - 1000, vocab, size=60, dtype=np.int64),
+                          rng.integers(0, 1000, size=40, dtype=np.int64)])
+    b = runner.sparse_buffers([runner.to_device(ids)], [runner.to_device(val[0])], dim, vocab, 5,
+                              px.PX_HASH_MUL)
+    runner.coalesce(ctx, b)
+    runner.partition(ctx, b)
+    u = int(b.out_num.item())
+    o_ids, o_rows, _ = oracle.sparse_coalesce([ids], val, dim, vocab)
+    assert np.array_equal(b.out_ids[:u].cpu().numpy(), o_ids)
+    close(b.out_rows[:u].cpu().numpy(), o_rows)
+    o_shard, o_perm, o_off = oracle.partition_rows(o_ids, 5, "mul")
+    assert np.array_equal(b.shard[:u].cpu().numpy(), o_shard)
+    assert np.array_equal(b.perm[:u].cpu().numpy(), o_perm)
+    assert np.array_equal(b.offsets.cpu().numpy(), o_off)
+
+
+def test_two_runs_give_the_same_bits(gpu):
+    ctx, px, runner = gpu
+    w = inputs.shrink(inputs.STRESS_ZIPF, vocab=100_000, n_workers=8, n_per_worker=5000)
+    d_idx = [runner.to_device(i) for i in inputs.sparse_ids(w)]
+    d_val = [runner.to_device(v) for v in inputs.sparse_values(w)]
+    outs = []
+    for _ in range(2):
+        b = runner.sparse_buffers(d_idx, d_val, w.dim, w.vocab, w.n_shards, px.PX_HASH_MUL)
+        runner.coalesce(ctx, b)
+        runner.partition(ctx, b)
+        u = int(b.out_num.item())
+        outs.append((b.out_ids[:u].clone(), b.out_rows[:u].clone(), b.perm[:u].clone()))
+    assert all(torch.equal(x, y) for x, y in zip(*outs))
+
+
+def test_out_of_range_id_raises_the_flag_and_protects_the_table(gpu):
+    ctx, px, runner = gpu
+    dim, vocab = 16, 100
+    for bad in (-1, vocab, 1 << 40):
+        ids = torch.tensor([3, 5, bad, 7], dtype=torch.int64, device="cuda")
+        val = torch.ones((4, dim), dtype=torch.float32, device="cuda")
+        b = runner.sparse_buffers([ids], [val], dim, vocab, 2, px.PX_HASH_MOD)
+        table = torch.randn(vocab, dim, device="cuda")
+        before = table.clone()
+        runner.sparse_step(ctx, b, table, None, "sgd", 0.5)
+        assert int(b.out_num.item()) == 0
+        assert torch.equal(table, before)
+        assert ctx.px_device_status() == px.PX_ERR_INDEX_OUT_OF_RANGE
+        assert ctx.px_device_status() == px.PX_OK          # reported once, then cleared
+    # apply checks the ids it is handed as well
+    ids = torch.tensor([1, vocab + 5], dtype=torch.int64, device="cuda")
+    rows = torch.ones((2, dim), dtype=torch.float32, device="cuda")
+    num = torch.tensor([2], dtype=torch.int64, device="cuda")
+    table = torch.zeros(vocab, dim, device="cuda")
+    ctx.px_sparse_apply_sgd(table, ids, rows, num, 2, None, None, 1.0)
+    assert ctx.px_device_status() == px.PX_ERR_INDEX_OUT_OF_RANGE
+    assert float(table[1, 0]) == -1.0 and float(table.abs().sum()) == dim
+
+
+def test_host_side_argument_errors(gpu):
+    ctx, px, runner = gpu
+    dim, vocab = 16, 100
+    ids = torch.zeros(10, dtype=torch.int64, device="cuda")
+    val = torch.zeros((10, dim), dtype=torch.float32, device="cuda")
+    b = runner.sparse_buffers([ids], [val], dim, vocab, 2, px.PX_HASH_MOD)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(px.PxError) as e:
+        ctx.px_sparse_coalesce(b.idx, b.val, dim, vocab, 1.0, b.out_ids, b.out_rows, b.out_num, None, small)
+    assert e.value.status == px.PX_ERR_SCRATCH_TOO_SMALL
+    with pytest.raises(px.PxError) as e:
+        ctx.px_sparse_coalesce(b.idx, b.val, dim, 0, 1.0, b.out_ids, b.out_rows, b.out_num, None, b.scratch)
+    assert e.value.status == px.PX_ERR_INVALID_ARG
+    with pytest.raises(px.PxError) as e:
+        ctx.px_partition_rows(b.out_ids, b.out_num, 10, px.PX_MAX_SHARDS + 1, px.PX_HASH_MOD, None, b.perm,
+                              b.offsets, b.part_scratch)
+    assert e.value.status == px.PX_ERR_INVALID_ARG
+
+
+# ---------------------------------------------------------------- partition
+
+@pytest.mark.parametrize("n_shards", [1, 2, 3, 7, 16, 100, 256])
+@pytest.mark.parametrize("hash_name", ["mod", "mul"])
+def test_partition_shard_counts(gpu, n_shards, hash_name):
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(n_shards)
+    ids = np.unique(rng.integers(0, 1 << 31, size=9000, dtype=np.int64))
+    cap = ids.size + 500                                   # capacity larger than the real count
+    d_ids = torch.zeros(cap, dtype=torch.int64, device="cuda")
+    d_ids[:ids.size] = torch.from_numpy(ids).cuda()
+    d_ids[ids.size:] = -12345                              # must never be looked at
+    num = torch.tensor([ids.size], dtype=torch.int64, device="cuda")
+    shard = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    perm = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    off = torch.empty(n_shards + 1, dtype=torch.int64, device="cuda")
+    scratch = px.alloc_scratch(px.Context.px_partition_scratch_bytes(cap))
+    code = px.PX_HASH_MUL if hash_name == "mul" else px.PX_HASH_MOD
+    ctx.px_partition_rows(d_ids, num, cap, n_shards, code, shard, perm, off, scratch)
+    o_shard, o_perm, o_off = oracle.partition_rows(ids, n_shards, hash_name)
+    assert np.array_equal(shard[:ids.size].cpu().numpy(), o_shard)
+    assert np.array_equal(perm[:ids.size].cpu().numpy(), o_perm)
+    assert np.array_equal(off.cpu().numpy(), o_off)
+    assert bool((shard[ids.size:] == -1).all()) and bool((perm[ids.size:] == -1).all())
+
+
+def test_apply_shard_by_shard_equals_apply_all(gpu):
+    ctx, px, runner = gpu
+    w = inputs.shrink(inputs.LARGE_LM, vocab=20_000, n_workers=8, n_per_worker=1000, dim=64)
+    d_idx = [runner.to_device(i) for i in inputs.sparse_ids(w)]
+    d_val = [runner.to_device(v) for v in inputs.sparse_values(w)]
+    b = runner.sparse_buffers(d_idx, d_val, w.dim, w.vocab, w.n_shards, px.PX_HASH_MUL)
+    runner.coalesce(ctx, b)
+    runner.partition(ctx, b)
+    t0 = torch.from_numpy(inputs.table_init(w)).cuda()
+    a0 = torch.from_numpy(inputs.accum_init(w)).cuda()
+    t_all, a_all = t0.clone(), a0.clone()
+    runner.apply(ctx, b, t_all, a_all, "adagrad", w.lr)
+    t_sh, a_sh = t0.clone(), a0.clone()
+    for p in range(w.n_shards):
+        runner.apply(ctx, b, t_sh, a_sh, "adagrad", w.lr, range_=b.offsets[p:p + 2])
+    assert torch.equal(t_all, t_sh) and torch.equal(a_all, a_sh)
+    assert not torch.equal(t_all, t0)
+    # one shard alone touches only ids of that shard
+    t_one = t0.clone()
+    runner.apply(ctx, b, t_one, a0.clone(), "adagrad", w.lr, range_=b.offsets[2:4])
+    changed = (t_one != t0).any(dim=1).nonzero().flatten().cpu().numpy()
+    assert changed.size > 0 and np.all((changed * 2654435761) % (1 << 64) % w.n_shards == 2)
+
+
+# --------------------------------------------------------------------- dense
+
+@pytest.mark.parametrize("n_buffers,count", [(1, 1000), (4, 65_536), (8, 4099), (48, 70_001), (65, 513),
+                                             (300, 2048)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_dense_average(gpu, n_buffers, count, bf16):
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(n_buffers + count)
+    bufs = [rng.standard_normal(count, dtype=np.float32) for _ in range(n_buffers)]
+    if bf16:
+        bufs = [inputs.f32_to_bf16_bits(b) for b in bufs]
+    d = [runner.to_device(b) for b in bufs]
+    out = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctx.px_dense_average(d, count, out, 1.0 / n_buffers)
+    close(out.cpu().numpy(), oracle.dense_average(bufs, average=True))
+    ctx.px_dense_average(d, count, out, 1.0)
+    close(out.cpu().numpy(), oracle.dense_average(bufs, average=False))
+    if n_buffers == 1 and not bf16:
+        assert np.array_equal(out.cpu().numpy(), bufs[0])
+
+
+def test_dense_average_bf16_output_and_unaligned(gpu):
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(21)
+    count, n = 5001, 6
+    bufs = [rng.standard_normal(count + 1, dtype=np.float32) for _ in range(n)]
+    d = [runner.to_device(b) for b in bufs]
+    ref = oracle.dense_average([b[1:] for b in bufs], average=True)
+    out = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctx.px_dense_average([x[1:] for x in d], count, out, 1.0 / n)          # 4-byte aligned only
+    close(out.cpu().numpy(), ref)
+    out16 = torch.empty(count, dtype=torch.bfloat16, device="cuda")
+    ctx.px_dense_average([x[1:] for x in d], count, out16, 1.0 / n)
+    ref16 = torch.from_numpy(ref).to(torch.bfloat16)
+    assert torch.equal(out16.cpu(), ref16)
+    aligned = [x[:count - 1].contiguous() for x in d]
+    ctx.px_dense_average(aligned, count - 1, out16, 1.0 / n)
+    ref16 = torch.from_numpy(oracle.dense_average([b[:count - 1] for b in bufs])).to(torch.bfloat16)
+    assert torch.equal(out16[:count - 1].cpu(), ref16)
+
+
+def test_dense_average_integers_are_exact(gpu):
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(22)
+    bufs = [inputs.small_integer_values(rng, (10_000,), -100, 100) for _ in range(16)]
+    out = torch.empty(10_000, dtype=torch.float32, device="cuda")
+    ctx.px_dense_average([runner.to_device(b) for b in bufs], 10_000, out, 1.0 / 16)
+    assert np.array_equal(out.cpu().numpy(), oracle.dense_average(bufs))
+
+
+def test_dense_average_full_size_sampled(gpu):
+    """48 x 64M bf16 (the NMT-like dense part) in the benchmark's launch shape; the oracle
+    recomputes three windows and a scattered sample of the outputs."""
+    ctx, px, runner = gpu
+    w = inputs.NMT
+    count = w.dense_count
+    block = inputs.dense_buffer(w, inputs.dense_rngs(w)[0], 1 << 22)       # 4M-element seeded block
+    base = runner.to_device(block)
+    g = torch.Generator(device="cuda").manual_seed(1808)
+    d = []
+    for k in range(w.n_workers):                                           # each worker: its own shuffle
+        shift = int(torch.randint(0, 1 << 22, (1,), generator=g, device="cuda").item())
+        d.append(torch.roll(base, shift).repeat(count >> 22))
+    out = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctx.px_dense_average(d, count, out, 1.0 / w.n_workers)
+    rng = np.random.default_rng(5)
+    picks = [np.arange(0, 4096), np.arange(count // 2 - 777, count // 2 + 777),
+             np.arange(count - 4096, count), np.sort(rng.integers(0, count, size=20_000))]
+    for sel in picks:
+        t = torch.from_numpy(sel).cuda()
+        host = [x[t].view(torch.int16).cpu().numpy().view(np.uint16) for x in d]
+        close(out[t].cpu().numpy(), oracle.dense_average(host, average=True), rel=1e-2)
+        close(out[t].cpu().numpy(), oracle.dense_average(host, average=True))
