@@ -1,0 +1,298 @@
+"""Benchmark of the sparse/dense gradient aggregation hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others] [--no-cpu]
+
+A step is one pass of the whole hot path over one batch of synthetic gradients:
+for every sparse variable coalesce -> partition -> apply, then the dense mean.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+The headline workload is the largest configuration (NMT-like: two 32,768 x 1,024
+tables with bf16 value rows from 48 workers, plus the mean of 48 bf16 buffers of
+64M elements).  The other configurations are timed briefly and reported inside
+"other_workloads" (sparse chain and dense mean separately).
+"""
+
+from __future__ import annotations
+
+import argparse
+import concurrent.futures
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="nmt_like")
+    ap.add_argument("--no-others", action="store_true", help="skip the brief runs of the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+# -------------------------------------------------------------- byte counting
+
+def sparse_bytes(m, u, dim, es, n_shards, optimizer):
+    """Algorithmic HBM bytes of coalesce, partition, apply for one table (unfused)."""
+    a1 = m * 8 + m * dim * es + u * 8 + u * dim * 4
+    a2 = u * 8 + u * 4 + (n_shards + 1) * 8
+    a3 = u * (8 + (12 if optimizer == "sgd" else 20) * dim)
+    return a1, a2, a3
+
+
+def dense_bytes(n, count, es, out_es=4):
+    return n * count * es + count * out_es
+
+
+# ------------------------------------------------------------------ workload
+
+class DeviceWorkload:
+    """A workload's inputs in HBM, `sets` rotating copies of the value rows (cold caches)."""
+
+    def __init__(self, w, ctx, sets=1, with_dense=True):
+        import torch
+        from paper_1808_02621_amd import inputs, px, runner
+        self.w, self.ctx, self.runner, self.torch = w, ctx, runner, torch
+        hash_code = px.PX_HASH_MUL if w.hash == "mul" else px.PX_HASH_MOD
+        self.host_idx, self.host_val, self.tables, self.accums, self.bufs = [], [], [], [], []
+        for t in range(w.n_tables):
+            idx = inputs.sparse_ids(w, t)
+            val = inputs.sparse_values(w, t)
+            self.host_idx.append(idx)
+            self.host_val.append(val)
+            d_idx = [runner.to_device(i) for i in idx]
+            per_set = []
+            for s in range(sets):
+                d_val = [runner.to_device(v) for v in val]
+                per_set.append(runner.sparse_buffers(d_idx, d_val, w.dim, w.vocab, w.n_shards, hash_code))
+            self.bufs.append(per_set)
+            table = torch.empty((w.vocab, w.dim), dtype=torch.float32, device="cuda")
+            table.normal_(0.0, inputs.TABLE_INIT_STD)           # timing only; parity runs use inputs.table_init
+            self.tables.append(table)
+            self.accums.append(torch.full((w.vocab, w.dim), w.accum_init, dtype=torch.float32, device="cuda")
+                               if w.optimizer == "adagrad" else None)
+        self.unique = []
+        self.dense = []
+        self.dense_out = None
+        if with_dense and w.dense_count:
+            rngs = inputs.dense_rngs(w)
+            with concurrent.futures.ThreadPoolExecutor(max_workers=8) as pool:
+                host = pool.map(lambda r: inputs.dense_buffer(w, r), rngs)
+                for h in host:
+                    self.dense.append(runner.to_device(h))
+            self.dense_out = torch.empty(w.dense_count, dtype=torch.float32, device="cuda")
+        self.step_no = 0
+
+    def sparse(self):
+        for t in range(self.w.n_tables):
+            b = self.bufs[t][self.step_no % len(self.bufs[t])]
+            self.runner.sparse_step(self.ctx, b, self.tables[t], self.accums[t], self.w.optimizer, self.w.lr)
+
+    def dense_mean(self):
+        if self.dense:
+            self.ctx.px_dense_average(self.dense, self.w.dense_count, self.dense_out, 1.0 / self.w.n_workers)
+
+    def step(self):
+        self.sparse()
+        self.dense_mean()
+        self.step_no += 1
+
+    def unique_counts(self):
+        self.torch.cuda.synchronize()
+        return [int(self.bufs[t][0].out_num.item()) for t in range(self.w.n_tables)]
+
+    def algorithmic_bytes(self):
+        w = self.w
+        es = 2 if w.val_dtype == "bf16" else 4
+        sp = 0
+        for u in self.unique_counts():
+            sp += sum(sparse_bytes(w.total_rows, u, w.dim, es, w.n_shards, w.optimizer))
+        dn = dense_bytes(w.n_workers, w.dense_count, 2 if w.dense_dtype == "bf16" else 4) if self.dense else 0
+        return sp, dn
+
+
+def timed(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def event_timed(torch, fn, steps, warmup):
+    """Average duration of fn's work on the current stream, from event pairs around each call."""
+    for _ in range(warmup):
+        fn()
+    pairs = []
+    for _ in range(steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    ms = [a.elapsed_time(b) for a, b in pairs]
+    return float(np.mean(ms)) * 1e-3, float(np.min(ms)) * 1e-3
+
+
+# -------------------------------------------------------------- CPU baseline
+
+def cpu_baseline(dw):
+    """The oracle, as it stands, on one host core: the whole sparse chain of every table plus
+    the dense mean on a 1/16 slice of each buffer (scaled up), as rows per second of a step."""
+    import oracle
+    w = dw.w
+    t0 = time.perf_counter()
+    for t in range(w.n_tables):
+        ids, rows, _ = oracle.sparse_coalesce(dw.host_idx[t], dw.host_val[t], w.dim, w.vocab)
+        _, perm, _ = oracle.partition_rows(ids, w.n_shards, w.hash)
+        table = np.zeros((w.vocab, w.dim), dtype=np.float32)
+        if w.optimizer == "sgd":
+            oracle.sparse_apply_sgd(table, ids, rows, w.lr, perm=perm)
+        else:
+            oracle.sparse_apply_adagrad(table, np.full_like(table, w.accum_init), ids, rows, w.lr, perm=perm)
+    t_sparse = time.perf_counter() - t0
+    t_dense, frac = 0.0, 16
+    if dw.dense:
+        n = w.dense_count // frac
+        host = [d[:n].view(dw.torch.int16).cpu().numpy().view(np.uint16) if w.dense_dtype == "bf16"
+                else d[:n].cpu().numpy() for d in dw.dense]
+        t0 = time.perf_counter()
+        oracle.dense_average(host, average=True)
+        t_dense = (time.perf_counter() - t0) * frac
+    total = t_sparse + t_dense
+    return {
+        "value": w.n_tables * w.total_rows / total, "unit": "rows/s", "cores": 1, "kind": "oracle",
+        "sample": "full sparse chain of %d table(s) (%.2f s) + dense mean on 1/%d of each buffer, scaled x%d "
+                  "(%.2f s)" % (w.n_tables, t_sparse, frac, frac, t_dense),
+        "seconds_per_step": total,
+    }
+
+
+# ---------------------------------------------------------------------- main
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused); "
+                 "the whole workload runs on cuda:0" % args.gpus)
+    import torch
+    from paper_1808_02621_amd import inputs, px
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    ctx = px.Context(0)
+    w = inputs.WORKLOADS[args.workload]
+
+    dw = DeviceWorkload(w, ctx, sets=1)
+    for _ in range(args.warmup):
+        dw.step()
+    assert ctx.px_device_status() == px.PX_OK
+    uniq = dw.unique_counts()
+    sp_bytes, dn_bytes = dw.algorithmic_bytes()
+
+    # the timed region: exactly K steps, with an event pair around the dominant kernel's call
+    dense_pairs = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dw.sparse()
+        if dw.dense:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            dw.dense_mean()
+            b.record()
+            dense_pairs.append((a, b))
+        dw.step_no += 1
+    torch.cuda.synchronize()
+    sec_per_step = (time.perf_counter() - t0) / args.steps
+
+    rows_per_step = w.n_tables * w.total_rows
+    result = {
+        "metric": "coalesced+applied gradient rows/sec and achieved HBM GB/s (% of peak), 1 GPU",
+        "value": rows_per_step / sec_per_step,
+        "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec_per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64 accumulate, f32 state (bf16 inputs)" if w.val_dtype == "bf16" else "f64 accumulate, f32 state",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name, "tables": w.n_tables, "vocab": w.vocab, "dim": w.dim,
+            "workers": w.n_workers, "rows_per_worker": w.n_per_worker, "zipf_s": w.zipf_s,
+            "value_dtype": w.val_dtype, "shards": w.n_shards, "optimizer": w.optimizer,
+            "dense_elements": w.dense_count, "dense_dtype": w.dense_dtype, "unique_rows": uniq,
+        },
+        "step_hbm_gbps": (sp_bytes + dn_bytes) / sec_per_step / 1e9,
+        "step_hbm_frac": (sp_bytes + dn_bytes) / sec_per_step / 1e9 / HBM_PEAK_GBPS,
+        "step_algorithmic_bytes": {"sparse": sp_bytes, "dense": dn_bytes},
+    }
+
+    if dense_pairs:
+        ms = [a.elapsed_time(b) for a, b in dense_pairs]
+        avg = float(np.mean(ms)) * 1e-3
+        result["roofline"] = {
+            "kernel": "k_dense_vec (px_dense_average)", "bound": "hbm",
+            "achieved": dn_bytes / avg / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": dn_bytes / avg / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+            "avg_launch_us": avg * 1e6, "algorithmic_bytes_per_launch": dn_bytes,
+        }
+    sparse_avg, sparse_min = event_timed(torch, dw.sparse, max(5, args.steps // 2), 2)
+    result["sparse_chain"] = {
+        "avg_us": sparse_avg * 1e6, "min_us": sparse_min * 1e6, "algorithmic_bytes": sp_bytes,
+        "achieved_gbps": sp_bytes / sparse_avg / 1e9, "frac": sp_bytes / sparse_avg / 1e9 / HBM_PEAK_GBPS,
+        "rows_per_s": rows_per_step / sparse_avg,
+    }
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(dw)
+    del dw
+    torch.cuda.empty_cache()
+
+    if not args.no_others:
+        others = {}
+        for name, ow in inputs.WORKLOADS.items():
+            if name == w.name:
+                continue
+            vbytes = ow.total_rows * ow.dim * (2 if ow.val_dtype == "bf16" else 4)
+            sets = int(min(4, max(1, (1 << 30) // max(vbytes, 1))))      # > 512 MB of value rows in rotation
+            odw = DeviceWorkload(ow, ctx, sets=sets)
+            odw.step()
+            obytes, odense = odw.algorithmic_bytes()
+
+            def sparse_rot(odw=odw):
+                odw.sparse()
+                odw.step_no += 1
+
+            s_avg, s_min = event_timed(torch, sparse_rot, 20, 4)
+            entry = {"unique_rows": odw.unique_counts(), "sparse_avg_us": s_avg * 1e6, "sparse_min_us": s_min * 1e6,
+                     "sparse_gbps": obytes / s_avg / 1e9, "sparse_frac": obytes / s_avg / 1e9 / HBM_PEAK_GBPS,
+                     "rows_per_s": ow.n_tables * ow.total_rows / s_avg}
+            if odw.dense:
+                d_avg, d_min = event_timed(torch, odw.dense_mean, 10, 2)
+                entry.update({"dense_avg_us": d_avg * 1e6, "dense_gbps": odense / d_avg / 1e9,
+                              "dense_frac": odense / d_avg / 1e9 / HBM_PEAK_GBPS})
+            others[name] = entry
+            del odw
+            torch.cuda.empty_cache()
+        result["other_workloads"] = others
+
+    assert ctx.px_device_status() == px.PX_OK
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
