@@ -7,39 +7,76 @@
 //              (ceil(log2 vocab) bits, 8 per pass); value rows never move
 //   3. heads   a row is a run head if its id differs from its predecessor's; counting and
 //              ranking the heads yields U, the distinct ids and every run's start
-//   4. segsum  the sorted order is cut into fixed tiles of rows; a lane group walks its tile,
-//              gathers each value row with 128-bit loads and accumulates in double.  Runs
-//              inside one tile are written out at once; a run that crosses a tile border
-//              leaves one double-precision partial row per tile
-//   5. fixup   each border-crossing run adds up its partial rows, rounds once, writes its row
-// Nothing waits on another workgroup and global atomics only append to the list of
-// border-crossing runs, so the sums are deterministic.
+//   4. segsum  the sorted order is cut into windows of T rows; tile t runs from the first head
+//              in window t to the first head in window t+1 (a window without a head keeps its
+//              own border), so only runs longer than a window are ever split.  A lane group
+//              walks its tile, gathers each value row with 128-bit loads and accumulates in
+//              double.  Whole runs are rounded and written at once; a split run leaves one
+//              double-precision partial row per tile
+//   5. fixup   each split run adds up its partial rows, rounds once, writes its row
+// Nothing waits on another workgroup and global atomics only append to the list of split
+// runs, so the sums are deterministic.
 #include "px_radix.h"
 
 namespace {
 
 // ------------------------------------------------------------------ geometry
 
-// Rows per segsum tile: enough tiles to fill the chip, few enough partial rows.
+// Rows per segsum window (a power of two that divides PX_SORT_TILE): enough tiles to fill the
+// chip, few enough partial rows.
 inline int tile_rows_for(int64_t m) {
-    int64_t t = (m + 8191) / 8192;
-    t = (t + 7) / 8 * 8;
-    if (t < 32) t = 32;
-    if (t > 256) t = 256;
-    return (int) t;
+    int t = 32;
+    while (t < 256 && (int64_t) t * 8192 < m) t <<= 1;
+    return t;
 }
+
+// How a row of `dim` elements is spread over a lane group: G lanes, C pieces per lane, E elements
+// per piece; rows wider than G*C pieces take several slabs (grid.y).
+struct RowShape {
+    int G, C, E, pieces, slabs;
+    int64_t pstride;        // doubles per partial row (padded to whole slabs)
+};
+
+inline RowShape row_shape(int64_t dim, int es, bool vec) {
+    RowShape r;
+    r.E = vec ? 16 / es : 1;
+    r.pieces = (int) (dim / r.E);
+    if (r.pieces <= 16) { r.G = 16; r.C = 1; }
+    else if (r.pieces <= 32) { r.G = 32; r.C = 1; }
+    else if (r.pieces <= 64) { r.G = 64; r.C = 1; }
+    else if (r.pieces <= 128) { r.G = 64; r.C = 2; }
+    else { r.G = 64; r.C = 4; }
+    r.slabs = (r.pieces + r.G * r.C - 1) / (r.G * r.C);
+    r.pstride = (int64_t) r.slabs * r.G * r.C * r.E;
+    return r;
+}
+
+inline int64_t max_partial_stride(int64_t dim) {
+    int64_t best = 0;
+    for (int es = 2; es <= 4; es += 2)
+        for (int vec = 0; vec < 2; ++vec) {
+            if (vec && (dim * es) % 16) continue;
+            const int64_t p = row_shape(dim, es, vec != 0).pstride;
+            if (p > best) best = p;
+        }
+    return best;
+}
+
+enum : uint32_t { TILE_STARTS_AT_HEAD = 0x80000000u, TILE_POS_MASK = 0x7fffffffu };
 
 struct Scratch {
     uint64_t* keys_a;
     uint64_t* keys_b;
     uint32_t* hist;        // [PX_SORT_MAX_BLOCKS][256]
+    uint32_t* totals;      // [256] items per digit
     uint32_t* hcount;      // heads per 2048-row block
     uint32_t* run_start;   // [M + 1]
-    uint32_t* tile_u0;     // run index of each tile's first row
-    uint32_t* span_list;   // runs that cross a tile border
+    uint32_t* tile_s;      // first row of each tile | TILE_STARTS_AT_HEAD
+    uint32_t* tile_u;      // run index of each tile's first row
+    uint32_t* span_list;   // runs split over several tiles
     uint32_t* counters;    // [0] = length of span_list
-    double* pfirst;        // [n_tiles][dim] partial of the run entering a tile
-    double* plast;         // [n_tiles][dim] partial of the run leaving a tile
+    double* pfirst;        // [n_tiles][pstride] partial of the run entering a tile
+    double* plast;         // [n_tiles][pstride] partial of the run leaving a tile
     size_t bytes;
 };
 
@@ -48,6 +85,7 @@ inline Scratch carve(void* base, int64_t m, int64_t dim) {
     const int t = tile_rows_for(m);
     const size_t n_tiles = (size_t) ((m + t - 1) / t);
     const size_t n_hblocks = (size_t) ((m + PX_SORT_TILE - 1) / PX_SORT_TILE);
+    const size_t pstride = (size_t) max_partial_stride(dim);
     size_t off = 0;
     char* b = (char*) base;
     auto take = [&](size_t bytes) {
@@ -58,13 +96,15 @@ inline Scratch carve(void* base, int64_t m, int64_t dim) {
     s.keys_a = (uint64_t*) take((size_t) m * 8);
     s.keys_b = (uint64_t*) take((size_t) m * 8);
     s.hist = (uint32_t*) take((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX * 4);
+    s.totals = (uint32_t*) take(PX_RADIX * 4);
     s.hcount = (uint32_t*) take((n_hblocks + 1) * 4);
     s.run_start = (uint32_t*) take(((size_t) m + 1) * 4);
-    s.tile_u0 = (uint32_t*) take((n_tiles + 1) * 4);
+    s.tile_s = (uint32_t*) take((n_tiles + 1) * 4);
+    s.tile_u = (uint32_t*) take((n_tiles + 1) * 4);
     s.span_list = (uint32_t*) take((n_tiles + 1) * 4);
     s.counters = (uint32_t*) take(64 * 4);
-    s.pfirst = (double*) take(n_tiles * (size_t) dim * 8);
-    s.plast = (double*) take(n_tiles * (size_t) dim * 8);
+    s.pfirst = (double*) take(n_tiles * pstride * 8);
+    s.plast = (double*) take(n_tiles * pstride * 8);
     s.bytes = off;
     return s;
 }
@@ -81,10 +121,10 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(const uint64_t* __rest
     __shared__ uint32_t s_prefix[PX_MAX_SOURCES + 1];
     __shared__ uint32_t s_hist[PX_RADIX];
     const int tid = threadIdx.x;
-    for (int i = tid; i <= n_workers; i += PX_SORT_THREADS) s_prefix[i] = (uint32_t) words[PXW_PREFIX + i];
+    for (int i = tid; i <= n_workers; i += PX_SORT_THREADS) s_prefix[i] = (uint32_t) words[2 * n_workers + i];
     s_hist[tid] = 0u;
     __syncthreads();
-    const int64_t* const* idx = (const int64_t* const*) (words + PXW_IDX_PTR);
+    const int64_t* const* idx = (const int64_t* const*) words;
     const int64_t begin = (int64_t) blockIdx.x * chunk;
     int64_t end = begin + chunk;
     if (end > m) end = m;
@@ -118,6 +158,7 @@ struct SortWords {
     __device__ uint32_t digit(Item v, int64_t) const { return (uint32_t) (v >> (32 + shift)) & 255u; }
     __device__ void note(int64_t, uint32_t) const {}
     __device__ void store(uint32_t dst, Item v) const { out[dst] = v; }
+    __device__ void publish(int, uint32_t, uint32_t) const {}
 };
 
 // --------------------------------------------------------------------- heads
@@ -140,22 +181,29 @@ __global__ __launch_bounds__(256) void k_heads_count(const uint64_t* __restrict_
     if (threadIdx.x == 0) hcount[blockIdx.x] = s_cnt;
 }
 
+// Ranks the heads: distinct ids, run starts, U; and for every window of tile_rows rows the tile
+// that starts there: its first row (the first head in the window, else the window's own first
+// row) and the run that row belongs to.
 __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__ sorted, int64_t m,
                                                     const uint32_t* __restrict__ hcount, int tile_rows,
                                                     int64_t* __restrict__ out_ids,
                                                     uint32_t* __restrict__ run_start,
-                                                    uint32_t* __restrict__ tile_u0,
+                                                    uint32_t* __restrict__ tile_s,
+                                                    uint32_t* __restrict__ tile_u,
                                                     int64_t* __restrict__ out_num_unique,
                                                     const uint32_t* __restrict__ flags) {
     __shared__ uint32_t s_wave[4];
+    __shared__ uint32_t s_first[PX_SORT_TILE / 32];        // first head of each window of this block
     const int tid = threadIdx.x;
+    if (tid < PX_SORT_TILE / 32) s_first[tid] = 0xffffffffu;
     // heads in all blocks before this one
     uint32_t part = 0;
     for (int b = tid; b < (int) blockIdx.x; b += 256) part += hcount[b];
     uint32_t before;
     pxr::block_exclusive_scan_256(part, s_wave, &before);
 
-    const int64_t base = (int64_t) blockIdx.x * PX_SORT_TILE + (int64_t) tid * PX_SORT_ITEMS;
+    const uint32_t block_base = blockIdx.x * (uint32_t) PX_SORT_TILE;
+    const int64_t base = (int64_t) block_base + (int64_t) tid * PX_SORT_ITEMS;
     uint32_t keys[PX_SORT_ITEMS];
     uint32_t flag[PX_SORT_ITEMS];
     uint32_t prev = 0;
@@ -170,22 +218,30 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
             keys[j] = key_of(sorted[i]);
             flag[j] = (i == 0 || keys[j] != prev) ? 1u : 0u;
             prev = keys[j];
+            if (flag[j]) atomicMin(&s_first[((uint32_t) i - block_base) / (uint32_t) tile_rows], (uint32_t) i);
         }
         cnt += flag[j];
     }
     uint32_t block_total;
-    uint32_t rank = before + pxr::block_exclusive_scan_256(cnt, s_wave, &block_total);
+    uint32_t rank = before + pxr::block_exclusive_scan_256(cnt, s_wave, &block_total);   // syncs
 #pragma unroll
     for (int j = 0; j < PX_SORT_ITEMS; ++j) {
         const int64_t i = base + j;
         if (i < m) {
+            const uint32_t w = ((uint32_t) i - block_base) / (uint32_t) tile_rows;
+            const uint32_t t = (uint32_t) i / (uint32_t) tile_rows;
             if (flag[j]) {
                 out_ids[rank] = (int64_t) keys[j];
                 run_start[rank] = (uint32_t) i;
+                if (s_first[w] == (uint32_t) i) {
+                    tile_s[t] = (uint32_t) i | TILE_STARTS_AT_HEAD;
+                    tile_u[t] = rank;
+                }
                 ++rank;
+            } else if ((uint32_t) i % (uint32_t) tile_rows == 0u && s_first[w] == 0xffffffffu) {
+                tile_s[t] = (uint32_t) i;          // window inside one run: the tile keeps its border
+                tile_u[t] = rank - 1u;             // the run row i belongs to
             }
-            if ((uint32_t) i % (uint32_t) tile_rows == 0u)
-                tile_u0[(uint32_t) i / (uint32_t) tile_rows] = rank - 1u;   // run that row i belongs to
         }
     }
     if (tid == 0 && (int64_t) (blockIdx.x + 1) * PX_SORT_TILE >= m) {     // block holding the last row
@@ -247,39 +303,49 @@ template <> struct RowLoad<uint16_t, false> {
 
 struct SegsumArgs {
     const uint64_t* sorted;       // packed words in id order
-    const uint64_t* words;        // context table: value base pointers
-    const uint32_t* tile_u0;
+    const uint64_t* words;        // context table: [idx pointers | value pointers | prefix]
+    const uint32_t* tile_s;
+    const uint32_t* tile_u;
     double* pfirst;
     double* plast;
     uint32_t* span_list;
     uint32_t* span_count;
     float* out_rows;
     int64_t m;
+    int64_t n_tiles;
     int64_t dim;                  // elements per row
     int64_t row_bytes;            // bytes per input row
+    int64_t pstride;              // doubles per partial row
     int n_workers;
     int local_bits;
-    int tile_rows;
     int pieces;                   // row pieces (E elements each) per row
     float scale;
 };
 
 // G lanes walk one tile; lane l owns pieces slab*G*C + c*G + l, c < C, E elements each.
-// B rows are in flight at once.
+// B rows are in flight at once.  A partial row is stored lane-interleaved so that every store
+// instruction writes one contiguous block: pair p of piece c sits at ((slab*C + c)*(E/2) + p)*G + l.
 template <typename T, bool VEC, int G, int C, int B>
 __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
     typedef RowLoad<T, VEC> L;
     enum { E = L::E };
     __shared__ uint64_t s_base[PX_MAX_SOURCES];
-    for (int i = threadIdx.x; i < a.n_workers; i += 256) s_base[i] = a.words[PXW_VAL_PTR + i];
+    for (int i = threadIdx.x; i < a.n_workers; i += 256) s_base[i] = a.words[a.n_workers + i];
     __syncthreads();
 
     const int gl = threadIdx.x % G;
     const int64_t tile = (int64_t) blockIdx.x * (256 / G) + threadIdx.x / G;
-    const int64_t s = tile * a.tile_rows;
-    if (s >= a.m) return;
-    int64_t e = s + a.tile_rows;
-    if (e > a.m) e = a.m;
+    if (tile >= a.n_tiles) return;
+    const uint32_t ts = a.tile_s[tile];
+    const int64_t s = (int64_t) (ts & TILE_POS_MASK);
+    bool started = (ts & TILE_STARTS_AT_HEAD) != 0u;
+    int64_t e = a.m;
+    bool next_is_head = true;
+    if (tile + 1 < a.n_tiles) {
+        const uint32_t tn = a.tile_s[tile + 1];
+        e = (int64_t) (tn & TILE_POS_MASK);
+        next_is_head = (tn & TILE_STARTS_AT_HEAD) != 0u;
+    }
 
     int piece[C];
     bool live[C];
@@ -296,9 +362,8 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
 #pragma unroll
         for (int x = 0; x < E; ++x) acc[c][x] = 0.0;
 
-    uint32_t u = a.tile_u0[tile];
+    uint32_t u = a.tile_u[tile];
     uint32_t cur = key_of(a.sorted[s]);
-    bool started = (s == 0) || key_of(a.sorted[s - 1]) != cur;
 
     auto flush = [&](bool ended) {
         if (started && ended) {
@@ -314,18 +379,22 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
                             *(float4*) (dst + (size_t) piece[c] * E + x) = o;
                         }
                     } else {
-#pragma unroll
-                        for (int x = 0; x < E; ++x) dst[(size_t) piece[c] * E + x] = (float) (acc[c][x] * a.scale);
+                        dst[piece[c]] = (float) (acc[c][0] * a.scale);
                     }
                 }
         } else {
-            double* dst = (started ? a.plast : a.pfirst) + (size_t) tile * a.dim;
+            double* dst = (started ? a.plast : a.pfirst) + (size_t) tile * a.pstride;
 #pragma unroll
-            for (int c = 0; c < C; ++c)
-                if (live[c]) {
+            for (int c = 0; c < C; ++c) {
+                const size_t sc = (size_t) blockIdx.y * C + c;
+                if (VEC) {
 #pragma unroll
-                    for (int x = 0; x < E; ++x) dst[(size_t) piece[c] * E + x] = acc[c][x];
+                    for (int x = 0; x < E; x += 2)
+                        *(double2*) (dst + ((sc * (E / 2) + x / 2) * G + gl) * 2) = make_double2(acc[c][x], acc[c][x + 1]);
+                } else {
+                    dst[sc * G + gl] = acc[c][0];
                 }
+            }
             if (started && gl == 0 && blockIdx.y == 0) {
                 uint32_t slot = atomicAdd(a.span_count, 1u);
                 a.span_list[slot] = u;
@@ -369,49 +438,91 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
             }
         }
     }
-    const bool ended = (e == a.m) || key_of(a.sorted[e]) != cur;
-    flush(ended);
+    flush(next_is_head);
 }
 
 // -------------------------------------------------------------------- fix-up
+// A run split over tiles a..b left partial rows plast[a], pfirst[a+1..b].  One block of 16
+// waves per split run and 64-double slab of the (lane-interleaved) partial row: wave w adds
+// parts w, w+16, ... in double, the 16 sums are added in wave order, the result is rounded once
+// and written to the column the slot stands for.
+enum { FIX_SPLITS = 16 };
 
-__global__ __launch_bounds__(256) void k_fixup(const uint32_t* __restrict__ span_list,
-                                               const uint32_t* __restrict__ span_count,
-                                               const uint32_t* __restrict__ run_start, int tile_rows,
-                                               int64_t dim, const double* __restrict__ pfirst,
-                                               const double* __restrict__ plast, float* __restrict__ out_rows,
-                                               float scale, int32_t* __restrict__ out_run_len,
-                                               const int64_t* __restrict__ num_unique) {
-    __shared__ double s_red[4][64];
+struct FixupArgs {
+    const uint32_t* span_list;
+    const uint32_t* span_count;
+    const uint32_t* run_start;
+    const double* pfirst;
+    const double* plast;
+    float* out_rows;
+    int32_t* out_run_len;
+    const int64_t* num_unique;
+    int64_t m;
+    int64_t dim;
+    int64_t pstride;
+    int tile_rows;
+    int G, C, E, pieces;
+    float scale;
+};
+
+__global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
+    __shared__ double s_red[FIX_SPLITS][64];
     const int lane = threadIdx.x & 63, split = threadIdx.x >> 6;
-    const int64_t col = (int64_t) blockIdx.y * 64 + lane;
-    const uint32_t count = span_count[0];
+    const int64_t pe = (int64_t) blockIdx.y * 64 + lane;          // slot in the partial row
+    // which column does slot pe hold?
+    const int pair = a.E >= 2 ? 2 : 1, halves = a.E >= 2 ? a.E / 2 : 1;
+    const int64_t idx2 = pe / pair;
+    const int l = (int) (idx2 % a.G);
+    const int64_t t = idx2 / a.G;
+    const int64_t sc = t / halves;
+    const int64_t piece = (sc / a.C) * a.G * a.C + (sc % a.C) * a.G + l;
+    const int64_t col = piece * a.E + (t % halves) * pair + pe % pair;
+    const bool live = pe < a.pstride && piece < a.pieces;
+
+    const uint32_t count = a.span_count[0];
     for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
-        const uint32_t u = span_list[i];
-        const uint32_t first_tile = run_start[u] / (uint32_t) tile_rows;
-        const uint32_t last_tile = (run_start[u + 1] - 1u) / (uint32_t) tile_rows;
+        const uint32_t u = a.span_list[i];
+        const uint32_t end = a.run_start[u + 1];
+        const uint32_t first_tile = a.run_start[u] / (uint32_t) a.tile_rows;
+        const uint32_t last_tile = ((int64_t) end == a.m) ? (end - 1u) / (uint32_t) a.tile_rows
+                                                          : end / (uint32_t) a.tile_rows - 1u;
         const uint32_t parts = last_tile - first_tile + 1u;
         double acc = 0.0;
-        if (col < dim) {
-#pragma unroll 4
-            for (uint32_t q = split; q < parts; q += 4) {
-                const double* src = (q == 0) ? plast + (size_t) first_tile * dim
-                                             : pfirst + (size_t) (first_tile + q) * dim;
-                acc += src[col];
+        if (live) {
+            uint32_t q = split;
+            for (; q + 7 * FIX_SPLITS < parts; q += 8 * FIX_SPLITS) {
+                double v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t qq = q + j * FIX_SPLITS;
+                    const double* src = (qq == 0) ? a.plast + (size_t) first_tile * a.pstride
+                                                  : a.pfirst + (size_t) (first_tile + qq) * a.pstride;
+                    v[j] = src[pe];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc += v[j];
+            }
+            for (; q < parts; q += FIX_SPLITS) {
+                const double* src = (q == 0) ? a.plast + (size_t) first_tile * a.pstride
+                                             : a.pfirst + (size_t) (first_tile + q) * a.pstride;
+                acc += src[pe];
             }
         }
         s_red[split][lane] = acc;
         __syncthreads();
-        if (split == 0 && col < dim) {
-            const double t = ((s_red[0][lane] + s_red[1][lane]) + s_red[2][lane]) + s_red[3][lane];
-            out_rows[(size_t) u * dim + col] = (float) (t * scale);
+        if (split == 0 && live) {
+            double tsum = 0.0;
+#pragma unroll
+            for (int w = 0; w < FIX_SPLITS; ++w) tsum += s_red[w][lane];
+            a.out_rows[(size_t) u * a.dim + col] = (float) (tsum * a.scale);
         }
         __syncthreads();
     }
-    if (out_run_len != nullptr && blockIdx.y == 0) {
-        const int64_t n = num_unique[0];
-        for (int64_t u = (int64_t) blockIdx.x * 256 + threadIdx.x; u < n; u += (int64_t) gridDim.x * 256)
-            out_run_len[u] = (int32_t) (run_start[u + 1] - run_start[u]);
+    if (a.out_run_len != nullptr && blockIdx.y == 0) {
+        const int64_t n = a.num_unique[0];
+        const int64_t stride = (int64_t) gridDim.x * blockDim.x;
+        for (int64_t u = (int64_t) blockIdx.x * blockDim.x + threadIdx.x; u < n; u += stride)
+            a.out_run_len[u] = (int32_t) (a.run_start[u + 1] - a.run_start[u]);
     }
 }
 
@@ -425,16 +536,13 @@ int bits_for(uint64_t max_value) {   // bits needed to write max_value
 }
 
 template <typename T, bool VEC>
-void launch_segsum(const SegsumArgs& a, int64_t n_tiles, hipStream_t stream) {
-    const int pieces = a.pieces;
-    auto grid = [&](int g, int c) {
-        return dim3((unsigned) ((n_tiles + (256 / g) - 1) / (256 / g)), (unsigned) ((pieces + g * c - 1) / (g * c)), 1);
-    };
-    if (pieces <= 16) k_segsum<T, VEC, 16, 1, 8><<<grid(16, 1), 256, 0, stream>>>(a);
-    else if (pieces <= 32) k_segsum<T, VEC, 32, 1, 8><<<grid(32, 1), 256, 0, stream>>>(a);
-    else if (pieces <= 64) k_segsum<T, VEC, 64, 1, 8><<<grid(64, 1), 256, 0, stream>>>(a);
-    else if (pieces <= 128) k_segsum<T, VEC, 64, 2, 8><<<grid(64, 2), 256, 0, stream>>>(a);
-    else k_segsum<T, VEC, 64, 4, 4><<<grid(64, 4), 256, 0, stream>>>(a);
+void launch_segsum(const SegsumArgs& a, const RowShape& sh, hipStream_t stream) {
+    const dim3 grid((unsigned) ((a.n_tiles + (256 / sh.G) - 1) / (256 / sh.G)), (unsigned) sh.slabs, 1);
+    if (sh.G == 16) k_segsum<T, VEC, 16, 1, 8><<<grid, 256, 0, stream>>>(a);
+    else if (sh.G == 32) k_segsum<T, VEC, 32, 1, 8><<<grid, 256, 0, stream>>>(a);
+    else if (sh.C == 1) k_segsum<T, VEC, 64, 1, 8><<<grid, 256, 0, stream>>>(a);
+    else if (sh.C == 2) k_segsum<T, VEC, 64, 2, 8><<<grid, 256, 0, stream>>>(a);
+    else k_segsum<T, VEC, 64, 4, 4><<<grid, 256, 0, stream>>>(a);
 }
 
 }  // namespace
@@ -499,12 +607,8 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
         run += counts[w];
     }
     host_words[3 * n_workers] = (uint64_t) run;
-    px_status st;
-    st = px_upload_words(ctx, ctx->d_words + PXW_IDX_PTR, host_words, n_workers, sc.counters, 64, stream);
-    if (st != PX_OK) return st;
-    st = px_upload_words(ctx, ctx->d_words + PXW_VAL_PTR, host_words + n_workers, n_workers, nullptr, 0, stream);
-    if (st != PX_OK) return st;
-    st = px_upload_words(ctx, ctx->d_words + PXW_PREFIX, host_words + 2 * n_workers, n_workers + 1, nullptr, 0, stream);
+    // one launch for N <= 85 workers: [idx pointers | value pointers | row prefix]
+    px_status st = px_upload_words(ctx, ctx->d_words, host_words, 3 * n_workers + 1, sc.counters, 64, stream);
     if (st != PX_OK) return st;
 
     const px_sort_geom g = px_sort_geometry(m);
@@ -518,7 +622,8 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
     for (int p = 0; p < passes; ++p) {
         SortWords pol{src, dst, m, 8 * p};
         if (p > 0) pxr::k_radix_hist<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, g.chunk);
-        pxr::k_radix_scatter<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, g.n_blocks, g.chunk);
+        pxr::k_radix_prefix<<<PX_RADIX / 4, 256, 0, stream>>>(sc.hist, g.n_blocks, sc.totals);
+        pxr::k_radix_scatter<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, sc.totals, g.chunk);
         uint64_t* t = src;
         src = dst;
         dst = t;
@@ -530,36 +635,54 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
     const int n_hblocks = (int) ((m + PX_SORT_TILE - 1) / PX_SORT_TILE);
     k_heads_count<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount);
     k_heads_emit<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount, tile_rows, out_ids, sc.run_start,
-                                                sc.tile_u0, out_num_unique, ctx->d_flags);
+                                                sc.tile_s, sc.tile_u, out_num_unique, ctx->d_flags);
 
+    const RowShape sh = row_shape(dim, (int) es, vec);
     SegsumArgs a;
     a.sorted = sorted;
     a.words = ctx->d_words;
-    a.tile_u0 = sc.tile_u0;
+    a.tile_s = sc.tile_s;
+    a.tile_u = sc.tile_u;
     a.pfirst = sc.pfirst;
     a.plast = sc.plast;
     a.span_list = sc.span_list;
     a.span_count = sc.counters;
     a.out_rows = out_rows;
     a.m = m;
+    a.n_tiles = n_tiles;
     a.dim = dim;
     a.row_bytes = dim * (int64_t) es;
+    a.pstride = sh.pstride;
     a.n_workers = n_workers;
     a.local_bits = local_bits;
-    a.tile_rows = tile_rows;
+    a.pieces = sh.pieces;
     a.scale = scale;
     if (vec) {
-        a.pieces = (int) (dim * es / 16);
-        if (val_dtype == PX_F32) launch_segsum<float, true>(a, n_tiles, stream);
-        else launch_segsum<uint16_t, true>(a, n_tiles, stream);
+        if (val_dtype == PX_F32) launch_segsum<float, true>(a, sh, stream);
+        else launch_segsum<uint16_t, true>(a, sh, stream);
     } else {
-        a.pieces = (int) dim;
-        if (val_dtype == PX_F32) launch_segsum<float, false>(a, n_tiles, stream);
-        else launch_segsum<uint16_t, false>(a, n_tiles, stream);
+        if (val_dtype == PX_F32) launch_segsum<float, false>(a, sh, stream);
+        else launch_segsum<uint16_t, false>(a, sh, stream);
     }
-    const unsigned fx = (unsigned) (n_tiles < 1024 ? n_tiles : 1024);
-    k_fixup<<<dim3(fx, (unsigned) ((dim + 63) / 64), 1), 256, 0, stream>>>(
-        sc.span_list, sc.counters, sc.run_start, tile_rows, dim, sc.pfirst, sc.plast, out_rows, scale,
-        out_run_len, out_num_unique);
+    FixupArgs f;
+    f.span_list = sc.span_list;
+    f.span_count = sc.counters;
+    f.run_start = sc.run_start;
+    f.pfirst = sc.pfirst;
+    f.plast = sc.plast;
+    f.out_rows = out_rows;
+    f.out_run_len = out_run_len;
+    f.num_unique = out_num_unique;
+    f.m = m;
+    f.dim = dim;
+    f.pstride = sh.pstride;
+    f.tile_rows = tile_rows;
+    f.G = sh.G;
+    f.C = sh.C;
+    f.E = sh.E;
+    f.pieces = sh.pieces;
+    f.scale = scale;
+    const unsigned fx = (unsigned) (n_tiles < 64 ? n_tiles : 64);
+    k_fixup<<<dim3(fx, (unsigned) ((sh.pstride + 63) / 64), 1), 64 * FIX_SPLITS, 0, stream>>>(f);
     return px_check_hip(ctx, hipGetLastError(), "coalesce launch");
 }

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ 
     enum { E = In<TIN>::E };
     const int64_t i = (int64_t) blockIdx.x * 256 + threadIdx.x;
     if (i >= pieces) return;
-    const uint4* const* bufs = (const uint4* const*) (words + PXW_IDX_PTR);
+    const uint4* const* bufs = (const uint4* const*) words;
     acc_t acc[E];
 #pragma unroll
     for (int x = 0; x < E; ++x) acc[x] = (acc_t) 0;
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void k_dense_scalar(const uint64_t* __restrict
                                                       float scale) {
     const int64_t i = first + (int64_t) blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
-    const TIN* const* bufs = (const TIN* const*) (words + PXW_IDX_PTR);
+    const TIN* const* bufs = (const TIN* const*) words;
     acc_t acc = (acc_t) 0;
     for (int w = 0; w < n_buffers; ++w) acc += (acc_t) In<TIN>::widen(bufs[w][i]);
     const float o = (float) (acc * (acc_t) scale);
@@ -146,7 +146,7 @@ extern "C" px_status px_dense_average(px_ctx* ctx, int n_buffers, const void* co
         if (((uintptr_t) bufs[w]) % 16) vec = false;
         host_words[w] = (uint64_t) (uintptr_t) bufs[w];
     }
-    px_status st = px_upload_words(ctx, ctx->d_words + PXW_IDX_PTR, host_words, n_buffers, nullptr, 0, stream);
+    px_status st = px_upload_words(ctx, ctx->d_words, host_words, n_buffers, nullptr, 0, stream);
     if (st != PX_OK) return st;
     if (in_dtype == PX_F32) {
         if (out_dtype == PX_F32) launch<float, false>(ctx, n_buffers, count, vec, out, scale, stream);

@@ -16,13 +16,9 @@ struct px_ctx {
     char err[512];
 };
 
-// Layout of d_words (64-bit words).
-enum {
-    PXW_IDX_PTR = 0,                        // idx[w]   (coalesce) / bufs[w] (dense)
-    PXW_VAL_PTR = PX_MAX_SOURCES,           // val[w]
-    PXW_PREFIX = 2 * PX_MAX_SOURCES,        // row prefix, n_workers + 1 entries
-    PXW_TOTAL = 3 * PX_MAX_SOURCES + 8
-};
+// d_words holds, per call, [idx pointers | value pointers | row prefix (n + 1)] for coalesce
+// and [buffer pointers] for the dense mean.
+enum { PXW_TOTAL = 3 * PX_MAX_SOURCES + 8 };
 
 enum { PXF_BAD_ID = 1u };                   // bits of d_flags[0]
 
@@ -37,13 +33,12 @@ px_status px_upload_words(px_ctx* ctx, uint64_t* dst, const uint64_t* host_words
 static inline size_t px_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---------------------------------------------------------------- radix passes
-// One stable 8-bit counting pass = a histogram kernel (per block, per digit) and
-// a scatter kernel that derives its own offsets from the histogram matrix.
+// One stable 8-bit counting pass = histogram per block, prefix over blocks, scatter.
 enum {
     PX_SORT_THREADS = 256,
     PX_SORT_ITEMS = 8,
     PX_SORT_TILE = PX_SORT_THREADS * PX_SORT_ITEMS,   // items ranked at once in LDS
-    PX_SORT_MAX_BLOCKS = 512,
+    PX_SORT_MAX_BLOCKS = 512,     // multiple of 64
     PX_RADIX = 256
 };
 

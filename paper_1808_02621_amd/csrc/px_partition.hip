@@ -4,8 +4,9 @@
 // disjoint sets so that aggregation and update run per partition.  A shard is
 // H(id) mod P; grouping the row positions by shard is one stable counting pass
 // with the shard number as the digit, so ascending ids stay ascending inside a
-// shard.  The number of ids is a device scalar: the grid is sized for the
-// capacity and every block clamps to the real count.
+// shard; the scan of the per-shard totals is the offsets array.  The number of
+// ids is a device scalar: the grid is sized for the capacity and every block
+// clamps to the real count.
 #include "px_radix.h"
 
 namespace {
@@ -19,6 +20,7 @@ struct ShardPass {
     int mul_hash;
     int32_t* out_perm;
     int32_t* out_shard;
+    int64_t* out_offsets;
 
     __device__ int64_t count() const {
         int64_t n = num[0];
@@ -37,26 +39,18 @@ struct ShardPass {
         if (out_shard) out_shard[i] = (int32_t) d;
     }
     __device__ void store(uint32_t dst, Item v) const { out_perm[dst] = (int32_t) v; }
+    // offsets[p] = ids in shards below p; offsets[P] = number of ids
+    __device__ void publish(int bin, uint32_t start, uint32_t grand) const {
+        if (bin < (int) n_shards) out_offsets[bin] = (int64_t) start;
+        if (bin == 0) out_offsets[n_shards] = (int64_t) grand;
+    }
 };
-
-// offsets[p] = number of ids in shards below p; offsets[P] = number of ids.
-__global__ __launch_bounds__(256) void k_shard_offsets(const uint32_t* __restrict__ hist, int n_blocks,
-                                                       int n_shards, int64_t* __restrict__ offsets) {
-    __shared__ uint32_t s_wave[4];
-    const int tid = threadIdx.x;
-    uint32_t total = 0;
-    for (int b = 0; b < n_blocks; ++b) total += hist[(size_t) b * PX_RADIX + tid];
-    uint32_t grand;
-    const uint32_t start = pxr::block_exclusive_scan_256(total, s_wave, &grand);
-    if (tid < n_shards) offsets[tid] = (int64_t) start;
-    if (tid == 0) offsets[n_shards] = (int64_t) grand;
-}
 
 }  // namespace
 
 extern "C" size_t px_partition_scratch_bytes(int64_t cap) {
     if (cap < 0) return 0;
-    return px_align_up((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX * 4, 256);
+    return px_align_up((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX * 4, 256) + px_align_up(PX_RADIX * 4, 256);
 }
 
 extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids,
@@ -76,11 +70,11 @@ extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const in
     if (scratch_bytes < need) return px_fail(ctx, PX_ERR_SCRATCH_TOO_SMALL, "scratch %zu < %zu bytes", scratch_bytes, need);
 
     uint32_t* hist = (uint32_t*) scratch;
+    uint32_t* totals = (uint32_t*) ((char*) scratch + px_align_up((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX * 4, 256));
     const px_sort_geom g = px_sort_geometry(cap);
-    ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard};
+    ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard, out_offsets};
     pxr::k_radix_hist<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.chunk);
-    k_shard_offsets<<<1, 256, 0, stream>>>(hist, g.n_blocks, num_shards, out_offsets);
-    if (cap > 0)
-        pxr::k_radix_scatter<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.n_blocks, g.chunk);
+    pxr::k_radix_prefix<<<PX_RADIX / 4, 256, 0, stream>>>(hist, g.n_blocks, totals);
+    pxr::k_radix_scatter<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, totals, g.chunk);
     return px_check_hip(ctx, hipGetLastError(), "partition launch");
 }

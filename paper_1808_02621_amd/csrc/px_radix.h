@@ -1,12 +1,13 @@
 // Stable 8-bit counting pass for wave64: the building block of the id sort
 // (least-significant-digit radix sort) and of the shard partition.
 //
-// A pass is two kernels and uses no atomics on global memory and no waiting
+// A pass is three kernels and uses no atomics on global memory and no waiting
 // between workgroups:
-//   hist     block b counts the digits of its chunk       -> hist[b][256]
-//   scatter  block b sums hist over all blocks (bin totals) and over the blocks
-//            before it, scans the totals, then ranks its chunk tile by tile in
-//            LDS and writes every item to its final place.
+//   hist     block b counts the digits of its chunk        -> hist[b][256]
+//   prefix   one wave per digit turns its column of hist into an exclusive prefix
+//            over the blocks and writes the digit's total  -> hist[b][256], totals[256]
+//   scatter  block b scans the totals, adds its own prefix row, then ranks its
+//            chunk tile by tile in LDS and writes every item to its final place.
 // Ranking inside a tile is by wave-wide digit matching (ballots), with one LDS
 // counter row per wave, so equal digits keep their input order.
 #ifndef PX_RADIX_H_
@@ -53,7 +54,9 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
     return base + incl - v;
 }
 
-// Policy P supplies: typedef Item; count(); load(i); digit(item, i); note(i, d); store(dst, item).
+// Policy P supplies: typedef Item; count(); load(i); digit(item, i); note(i, d); store(dst, item);
+// publish(bin, start, grand): called once per bin by block 0 of the scatter with the bin's first
+// output position and the item count.
 
 template <class P>
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_hist(P p, uint32_t* __restrict__ hist,
@@ -75,9 +78,37 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_hist(P p, uint32_t* _
     hist[(size_t) blockIdx.x * PX_RADIX + tid] = s_hist[tid];
 }
 
+// hist[b][bin] <- sum of hist[b'][bin] over b' < b;  totals[bin] <- sum over all blocks.
+// Grid: PX_RADIX / 4 blocks of 256 threads, one wave per bin; lane l owns blocks [l*per, (l+1)*per).
+static __global__ __launch_bounds__(256) void k_radix_prefix(uint32_t* __restrict__ hist, int n_blocks,
+                                                      uint32_t* __restrict__ totals) {
+    enum { PER = (PX_SORT_MAX_BLOCKS + 63) / 64 };
+    const uint32_t lane = lane_id();
+    const int bin = (int) blockIdx.x * 4 + (int) (threadIdx.x >> 6);
+    uint32_t v[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        const int b = (int) lane * PER + j;
+        v[j] = b < n_blocks ? hist[(size_t) b * PX_RADIX + bin] : 0u;
+    }
+    uint32_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) sum += v[j];
+    const uint32_t incl = wave_inclusive_scan(sum);
+    uint32_t run = incl - sum;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        const int b = (int) lane * PER + j;
+        if (b < n_blocks) hist[(size_t) b * PX_RADIX + bin] = run;
+        run += v[j];
+    }
+    if (lane == 63) totals[bin] = incl;
+}
+
 template <class P>
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const uint32_t* __restrict__ hist,
-                                                                   int n_blocks, int64_t chunk) {
+                                                                   const uint32_t* __restrict__ totals,
+                                                                   int64_t chunk) {
     typedef typename P::Item Item;
     __shared__ Item s_items[PX_SORT_TILE];
     __shared__ uint8_t s_dig[PX_SORT_TILE];
@@ -92,14 +123,10 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
     const uint64_t below = lanes_below();
 
     // Where bin `tid` of this block starts in the output.
-    uint32_t total = 0, before = 0;
-    for (int b = 0; b < n_blocks; ++b) {
-        uint32_t v = hist[(size_t) b * PX_RADIX + tid];
-        total += v;
-        if (b < (int) blockIdx.x) before += v;
-    }
     uint32_t grand;
-    uint32_t gpos = block_exclusive_scan_256(total, s_wave, &grand) + before;
+    const uint32_t bin_start = block_exclusive_scan_256(totals[tid], s_wave, &grand);
+    uint32_t gpos = bin_start + hist[(size_t) blockIdx.x * PX_RADIX + tid];
+    if (blockIdx.x == 0) p.publish(tid, bin_start, grand);
 
     const int64_t n = p.count();
     const int64_t begin = (int64_t) blockIdx.x * chunk;
