@@ -122,15 +122,36 @@ class DeviceWorkload:
         return sp, dn
 
 
-def timed(torch, fn, steps, warmup):
-    for _ in range(warmup):
-        fn()
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % (kernel, workload))
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1]))
+    except OSError:
+        pass
+    return None
+
+
+def copy_calibration(torch, nbytes=1 << 30, reps=5):
+    """A plain device copy of known size: what a streaming kernel reaches on this machine, and the
+    reference the profiler's FETCH_SIZE / WRITE_SIZE counters are scaled by."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        fn()
+    pairs = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        dst.copy_(src)
+        b.record()
+        pairs.append((a, b))
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    sec = min(a.elapsed_time(b) for a, b in pairs) * 1e-3
+    return {"kernel": "torch copy_, %d MiB read + %d MiB written" % (nbytes >> 20, nbytes >> 20),
+            "gbps": 2 * nbytes / sec / 1e9, "frac_of_peak": 2 * nbytes / sec / 1e9 / HBM_PEAK_GBPS}
 
 
 def event_timed(torch, fn, steps, warmup):
@@ -197,6 +218,7 @@ def main():
     ctx = px.Context(0)
     w = inputs.WORKLOADS[args.workload]
 
+    calibration = copy_calibration(torch)
     dw = DeviceWorkload(w, ctx, sets=1)
     for _ in range(args.warmup):
         dw.step()
@@ -247,7 +269,7 @@ def main():
         result["roofline"] = {
             "kernel": "k_dense_vec (px_dense_average)", "bound": "hbm",
             "achieved": dn_bytes / avg / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": dn_bytes / avg / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+            "frac": dn_bytes / avg / 1e9 / HBM_PEAK_GBPS, "traffic": measured_traffic("k_dense_vec", w.name),
             "avg_launch_us": avg * 1e6, "algorithmic_bytes_per_launch": dn_bytes,
         }
     sparse_avg, sparse_min = event_timed(torch, dw.sparse, max(5, args.steps // 2), 2)
@@ -257,6 +279,7 @@ def main():
         "rows_per_s": rows_per_step / sparse_avg,
     }
 
+    result["copy_calibration"] = calibration
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(dw)
     del dw

@@ -7,9 +7,10 @@
 //              (ceil(log2 vocab) bits, 8 per pass); value rows never move
 //   3. heads   a row is a run head if its id differs from its predecessor's; counting and
 //              ranking the heads yields U, the distinct ids and every run's start
-//   4. segsum  the sorted order is cut into windows of T rows; tile t runs from the first head
-//              in window t to the first head in window t+1 (a window without a head keeps its
-//              own border), so only runs longer than a window are ever split.  A lane group
+//   4. segsum  the sorted order is cut into windows of T rows; tile t starts at the first head
+//              in the leading quarter of window t (else at the window's own border) and ends
+//              where tile t+1 starts, so the short runs that dominate never straddle two tiles
+//              and tiles stay within T/4 rows of each other in length.  A lane group
 //              walks its tile, gathers each value row with 128-bit loads and accumulates in
 //              double.  Whole runs are rounded and written at once; a split run leaves one
 //              double-precision partial row per tile
@@ -22,11 +23,28 @@ namespace {
 
 // ------------------------------------------------------------------ geometry
 
+// Tuning constants (overridable at compile time for experiments).
+#ifndef PX_TILE_MIN
+#define PX_TILE_MIN 32          // smallest segsum window, rows
+#endif
+#ifndef PX_TILE_MAX
+#define PX_TILE_MAX 256         // largest segsum window, rows
+#endif
+#ifndef PX_TILE_TARGET
+#define PX_TILE_TARGET 8192     // grow the window until there are at most this many tiles
+#endif
+#ifndef PX_ALIGN_DIV
+#define PX_ALIGN_DIV 4          // a tile moves to a head only within the first 1/PX_ALIGN_DIV of its window
+#endif
+
+static_assert(PX_TILE_MIN >= 32 && (PX_TILE_MIN & (PX_TILE_MIN - 1)) == 0 && PX_TILE_MAX <= PX_SORT_TILE,
+              "segsum windows are powers of two between 32 rows and one sort tile");
+
 // Rows per segsum window (a power of two that divides PX_SORT_TILE): enough tiles to fill the
 // chip, few enough partial rows.
 inline int tile_rows_for(int64_t m) {
-    int t = 32;
-    while (t < 256 && (int64_t) t * 8192 < m) t <<= 1;
+    int t = PX_TILE_MIN;
+    while (t < PX_TILE_MAX && (int64_t) t * PX_TILE_TARGET < m) t <<= 1;
     return t;
 }
 
@@ -182,8 +200,8 @@ __global__ __launch_bounds__(256) void k_heads_count(const uint64_t* __restrict_
 }
 
 // Ranks the heads: distinct ids, run starts, U; and for every window of tile_rows rows the tile
-// that starts there: its first row (the first head in the window, else the window's own first
-// row) and the run that row belongs to.
+// that starts there: its first row (the first head in the leading part of the window, else the
+// window's own first row) and the run that row belongs to.
 __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__ sorted, int64_t m,
                                                     const uint32_t* __restrict__ hcount, int tile_rows,
                                                     int64_t* __restrict__ out_ids,
@@ -204,6 +222,8 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
 
     const uint32_t block_base = blockIdx.x * (uint32_t) PX_SORT_TILE;
     const int64_t base = (int64_t) block_base + (int64_t) tid * PX_SORT_ITEMS;
+    // A head at a window's first row always starts the tile (align_rows >= 1), so every tile gets a start.
+    const uint32_t align_rows = (uint32_t) tile_rows / PX_ALIGN_DIV > 0u ? (uint32_t) tile_rows / PX_ALIGN_DIV : 1u;
     uint32_t keys[PX_SORT_ITEMS];
     uint32_t flag[PX_SORT_ITEMS];
     uint32_t prev = 0;
@@ -218,7 +238,8 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
             keys[j] = key_of(sorted[i]);
             flag[j] = (i == 0 || keys[j] != prev) ? 1u : 0u;
             prev = keys[j];
-            if (flag[j]) atomicMin(&s_first[((uint32_t) i - block_base) / (uint32_t) tile_rows], (uint32_t) i);
+            if (flag[j] && (uint32_t) i % (uint32_t) tile_rows < align_rows)
+                atomicMin(&s_first[((uint32_t) i - block_base) / (uint32_t) tile_rows], (uint32_t) i);
         }
         cnt += flag[j];
     }
@@ -239,7 +260,7 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
                 }
                 ++rank;
             } else if ((uint32_t) i % (uint32_t) tile_rows == 0u && s_first[w] == 0xffffffffu) {
-                tile_s[t] = (uint32_t) i;          // window inside one run: the tile keeps its border
+                tile_s[t] = (uint32_t) i;          // no head to move to: the tile keeps its border
                 tile_u[t] = rank - 1u;             // the run row i belongs to
             }
         }
@@ -449,6 +470,7 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
 enum { FIX_SPLITS = 16 };
 
 struct FixupArgs {
+    const uint32_t* tile_s;
     const uint32_t* span_list;
     const uint32_t* span_count;
     const uint32_t* run_start;
@@ -484,8 +506,8 @@ __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
         const uint32_t u = a.span_list[i];
         const uint32_t end = a.run_start[u + 1];
         const uint32_t first_tile = a.run_start[u] / (uint32_t) a.tile_rows;
-        const uint32_t last_tile = ((int64_t) end == a.m) ? (end - 1u) / (uint32_t) a.tile_rows
-                                                          : end / (uint32_t) a.tile_rows - 1u;
+        uint32_t last_tile = (end - 1u) / (uint32_t) a.tile_rows;       // tile holding the run's last row
+        if ((a.tile_s[last_tile] & TILE_POS_MASK) > end - 1u) --last_tile;
         const uint32_t parts = last_tile - first_tile + 1u;
         double acc = 0.0;
         if (live) {
@@ -665,6 +687,7 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
         else launch_segsum<uint16_t, false>(a, sh, stream);
     }
     FixupArgs f;
+    f.tile_s = sc.tile_s;
     f.span_list = sc.span_list;
     f.span_count = sc.counters;
     f.run_start = sc.run_start;

@@ -15,7 +15,22 @@ typedef float acc_t;
 typedef double acc_t;
 #endif
 
-enum { DENSE_BATCH = 8 };
+#ifndef PX_DENSE_BATCH
+#define PX_DENSE_BATCH 8        // loads in flight per thread
+#endif
+enum { DENSE_BATCH = PX_DENSE_BATCH };
+
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+// Every input byte is read exactly once: non-temporal loads keep the stream out of the caches.
+__device__ __forceinline__ uint4 load16(const uint4* p) {
+#ifdef PX_DENSE_TEMPORAL
+    return *p;
+#else
+    v4u v = __builtin_nontemporal_load((const v4u*) p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+#endif
+}
 
 __device__ __forceinline__ uint16_t to_bf16(float f) {   // round to nearest, ties to even
     uint32_t u = __float_as_uint(f);
@@ -64,7 +79,7 @@ __global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ 
         uint4 r[DENSE_BATCH];
 #pragma unroll
         for (int j = 0; j < DENSE_BATCH; ++j)
-            if (w0 + j < n_buffers) r[j] = bufs[w0 + j][i];
+            if (w0 + j < n_buffers) r[j] = load16(bufs[w0 + j] + i);
 #pragma unroll
         for (int j = 0; j < DENSE_BATCH; ++j)
             if (w0 + j < n_buffers) In<TIN>::add(acc, r[j]);

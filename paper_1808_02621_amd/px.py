@@ -15,7 +15,8 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIBRARY = os.path.join(_HERE, "libpx.so")
+# PX_LIBRARY may name another build of the same library (e.g. one compiled with other tuning macros).
+LIBRARY = os.environ.get("PX_LIBRARY") or os.path.join(_HERE, "libpx.so")
 
 PX_OK = 0
 PX_ERR_INVALID_ARG = 1
