@@ -80,7 +80,13 @@ inline int64_t max_partial_stride(int64_t dim) {
     return best;
 }
 
-enum : uint32_t { TILE_STARTS_AT_HEAD = 0x80000000u, TILE_POS_MASK = 0x7fffffffu };
+// Per tile: x = first row, y = flags, z = run index of the first row.
+enum : uint32_t {
+    TILE_STARTS_AT_HEAD = 1u,   // the first row is a run head
+    TILE_HAS_HEAD = 2u          // some row of the tile's window is a run head
+};
+// A split run: x = run index, y = tile holding its first row, z = tile holding its last row.
+enum { SPAN_LONG_TILES = 32 };  // runs over more tiles than this get a whole workgroup in the fix-up
 
 struct Scratch {
     uint64_t* keys_a;
@@ -89,10 +95,10 @@ struct Scratch {
     uint32_t* totals;      // [256] items per digit
     uint32_t* hcount;      // heads per 2048-row block
     uint32_t* run_start;   // [M + 1]
-    uint32_t* tile_s;      // first row of each tile | TILE_STARTS_AT_HEAD
-    uint32_t* tile_u;      // run index of each tile's first row
-    uint32_t* span_list;   // runs split over several tiles
-    uint32_t* counters;    // [0] = length of span_list
+    uint4* tile_info;      // [n_tiles] first row, flags, run index of the first row
+    uint4* span_long;      // [n_tiles] split runs over more than SPAN_LONG_TILES tiles
+    uint4* span_short;     // [n_tiles] the other split runs
+    uint32_t* counters;    // [0] = length of span_long, [1] = length of span_short
     double* pfirst;        // [n_tiles][pstride] partial of the run entering a tile
     double* plast;         // [n_tiles][pstride] partial of the run leaving a tile
     size_t bytes;
@@ -117,9 +123,9 @@ inline Scratch carve(void* base, int64_t m, int64_t dim) {
     s.totals = (uint32_t*) take(PX_RADIX * 4);
     s.hcount = (uint32_t*) take((n_hblocks + 1) * 4);
     s.run_start = (uint32_t*) take(((size_t) m + 1) * 4);
-    s.tile_s = (uint32_t*) take((n_tiles + 1) * 4);
-    s.tile_u = (uint32_t*) take((n_tiles + 1) * 4);
-    s.span_list = (uint32_t*) take((n_tiles + 1) * 4);
+    s.tile_info = (uint4*) take((n_tiles + 1) * 16);
+    s.span_long = (uint4*) take((n_tiles + 1) * 16);
+    s.span_short = (uint4*) take((n_tiles + 1) * 16);
     s.counters = (uint32_t*) take(64 * 4);
     s.pfirst = (double*) take(n_tiles * pstride * 8);
     s.plast = (double*) take(n_tiles * pstride * 8);
@@ -201,19 +207,22 @@ __global__ __launch_bounds__(256) void k_heads_count(const uint64_t* __restrict_
 
 // Ranks the heads: distinct ids, run starts, U; and for every window of tile_rows rows the tile
 // that starts there: its first row (the first head in the leading part of the window, else the
-// window's own first row) and the run that row belongs to.
+// window's own first row), the run that row belongs to, and whether the window holds any head.
 __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__ sorted, int64_t m,
                                                     const uint32_t* __restrict__ hcount, int tile_rows,
                                                     int64_t* __restrict__ out_ids,
                                                     uint32_t* __restrict__ run_start,
-                                                    uint32_t* __restrict__ tile_s,
-                                                    uint32_t* __restrict__ tile_u,
+                                                    uint4* __restrict__ tile_info,
                                                     int64_t* __restrict__ out_num_unique,
                                                     const uint32_t* __restrict__ flags) {
     __shared__ uint32_t s_wave[4];
-    __shared__ uint32_t s_first[PX_SORT_TILE / 32];        // first head of each window of this block
+    __shared__ uint32_t s_first[PX_SORT_TILE / 32];        // first aligning head of each window of this block
+    __shared__ uint32_t s_any[PX_SORT_TILE / 32];          // does the window hold a head at all
     const int tid = threadIdx.x;
-    if (tid < PX_SORT_TILE / 32) s_first[tid] = 0xffffffffu;
+    if (tid < PX_SORT_TILE / 32) {
+        s_first[tid] = 0xffffffffu;
+        s_any[tid] = 0u;
+    }
     // heads in all blocks before this one
     uint32_t part = 0;
     for (int b = tid; b < (int) blockIdx.x; b += 256) part += hcount[b];
@@ -238,8 +247,11 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
             keys[j] = key_of(sorted[i]);
             flag[j] = (i == 0 || keys[j] != prev) ? 1u : 0u;
             prev = keys[j];
-            if (flag[j] && (uint32_t) i % (uint32_t) tile_rows < align_rows)
-                atomicMin(&s_first[((uint32_t) i - block_base) / (uint32_t) tile_rows], (uint32_t) i);
+            if (flag[j]) {
+                const uint32_t w = ((uint32_t) i - block_base) / (uint32_t) tile_rows;
+                s_any[w] = 1u;
+                if ((uint32_t) i % (uint32_t) tile_rows < align_rows) atomicMin(&s_first[w], (uint32_t) i);
+            }
         }
         cnt += flag[j];
     }
@@ -254,14 +266,12 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
             if (flag[j]) {
                 out_ids[rank] = (int64_t) keys[j];
                 run_start[rank] = (uint32_t) i;
-                if (s_first[w] == (uint32_t) i) {
-                    tile_s[t] = (uint32_t) i | TILE_STARTS_AT_HEAD;
-                    tile_u[t] = rank;
-                }
+                if (s_first[w] == (uint32_t) i)
+                    tile_info[t] = make_uint4((uint32_t) i, TILE_STARTS_AT_HEAD | TILE_HAS_HEAD, rank, 0u);
                 ++rank;
             } else if ((uint32_t) i % (uint32_t) tile_rows == 0u && s_first[w] == 0xffffffffu) {
-                tile_s[t] = (uint32_t) i;          // no head to move to: the tile keeps its border
-                tile_u[t] = rank - 1u;             // the run row i belongs to
+                // no head to move to: the tile keeps its border and continues the run row i belongs to
+                tile_info[t] = make_uint4((uint32_t) i, s_any[w] ? TILE_HAS_HEAD : 0u, rank - 1u, 0u);
             }
         }
     }
@@ -278,59 +288,71 @@ __global__ void k_write_zero_count(int64_t* out_num_unique) {
 
 // -------------------------------------------------------------------- segsum
 
+#ifndef PX_SEG_ACC
+#define PX_SEG_ACC double       // accumulator type of the segmented sum
+#endif
+#ifndef PX_SEG_ROWS
+#define PX_SEG_ROWS 8           // rows in flight per lane group (up to two pieces per lane)
+#endif
+#ifndef PX_SEG_ROWS_WIDE
+#define PX_SEG_ROWS_WIDE 4      // rows in flight per lane group (four pieces per lane)
+#endif
+typedef PX_SEG_ACC seg_acc_t;
+
 template <typename T, bool VEC> struct RowLoad;
 
 template <> struct RowLoad<float, true> {
     typedef uint4 Raw;
     enum { E = 4 };
     static __device__ __forceinline__ Raw load(const char* p) { return *(const uint4*) p; }
-    static __device__ __forceinline__ void add(double* acc, const Raw& r) {
-        acc[0] += (double) __uint_as_float(r.x);
-        acc[1] += (double) __uint_as_float(r.y);
-        acc[2] += (double) __uint_as_float(r.z);
-        acc[3] += (double) __uint_as_float(r.w);
+    static __device__ __forceinline__ void add(seg_acc_t* acc, const Raw& r) {
+        acc[0] += (seg_acc_t) __uint_as_float(r.x);
+        acc[1] += (seg_acc_t) __uint_as_float(r.y);
+        acc[2] += (seg_acc_t) __uint_as_float(r.z);
+        acc[3] += (seg_acc_t) __uint_as_float(r.w);
     }
 };
 template <> struct RowLoad<float, false> {
     typedef float Raw;
     enum { E = 1 };
     static __device__ __forceinline__ Raw load(const char* p) { return *(const float*) p; }
-    static __device__ __forceinline__ void add(double* acc, const Raw& r) { acc[0] += (double) r; }
+    static __device__ __forceinline__ void add(seg_acc_t* acc, const Raw& r) { acc[0] += (seg_acc_t) r; }
 };
 // bfloat16 is the upper half of a float32: widening is a shift.
 template <> struct RowLoad<uint16_t, true> {
     typedef uint4 Raw;
     enum { E = 8 };
     static __device__ __forceinline__ Raw load(const char* p) { return *(const uint4*) p; }
-    static __device__ __forceinline__ void add(double* acc, const Raw& r) {
-        acc[0] += (double) __uint_as_float(r.x << 16);
-        acc[1] += (double) __uint_as_float(r.x & 0xffff0000u);
-        acc[2] += (double) __uint_as_float(r.y << 16);
-        acc[3] += (double) __uint_as_float(r.y & 0xffff0000u);
-        acc[4] += (double) __uint_as_float(r.z << 16);
-        acc[5] += (double) __uint_as_float(r.z & 0xffff0000u);
-        acc[6] += (double) __uint_as_float(r.w << 16);
-        acc[7] += (double) __uint_as_float(r.w & 0xffff0000u);
+    static __device__ __forceinline__ void add(seg_acc_t* acc, const Raw& r) {
+        acc[0] += (seg_acc_t) __uint_as_float(r.x << 16);
+        acc[1] += (seg_acc_t) __uint_as_float(r.x & 0xffff0000u);
+        acc[2] += (seg_acc_t) __uint_as_float(r.y << 16);
+        acc[3] += (seg_acc_t) __uint_as_float(r.y & 0xffff0000u);
+        acc[4] += (seg_acc_t) __uint_as_float(r.z << 16);
+        acc[5] += (seg_acc_t) __uint_as_float(r.z & 0xffff0000u);
+        acc[6] += (seg_acc_t) __uint_as_float(r.w << 16);
+        acc[7] += (seg_acc_t) __uint_as_float(r.w & 0xffff0000u);
     }
 };
 template <> struct RowLoad<uint16_t, false> {
     typedef uint16_t Raw;
     enum { E = 1 };
     static __device__ __forceinline__ Raw load(const char* p) { return *(const uint16_t*) p; }
-    static __device__ __forceinline__ void add(double* acc, const Raw& r) {
-        acc[0] += (double) __uint_as_float((uint32_t) r << 16);
+    static __device__ __forceinline__ void add(seg_acc_t* acc, const Raw& r) {
+        acc[0] += (seg_acc_t) __uint_as_float((uint32_t) r << 16);
     }
 };
 
 struct SegsumArgs {
     const uint64_t* sorted;       // packed words in id order
     const uint64_t* words;        // context table: [idx pointers | value pointers | prefix]
-    const uint32_t* tile_s;
-    const uint32_t* tile_u;
+    const uint4* tile_info;
+    const uint32_t* run_start;
     double* pfirst;
     double* plast;
-    uint32_t* span_list;
-    uint32_t* span_count;
+    uint4* span_long;
+    uint4* span_short;
+    uint32_t* counters;
     float* out_rows;
     int64_t m;
     int64_t n_tiles;
@@ -339,6 +361,7 @@ struct SegsumArgs {
     int64_t pstride;              // doubles per partial row
     int n_workers;
     int local_bits;
+    int tile_rows;
     int pieces;                   // row pieces (E elements each) per row
     float scale;
 };
@@ -346,27 +369,43 @@ struct SegsumArgs {
 // G lanes walk one tile; lane l owns pieces slab*G*C + c*G + l, c < C, E elements each.
 // B rows are in flight at once.  A partial row is stored lane-interleaved so that every store
 // instruction writes one contiguous block: pair p of piece c sits at ((slab*C + c)*(E/2) + p)*G + l.
+//
+// A block holds 256/G consecutive tiles.  When all of them lie strictly inside one run (none of
+// their windows holds a head and the run goes on into the next block) their partial rows are
+// added in LDS, in tile order, and stored once, as the partial row of the block's first tile: a
+// long run then leaves one partial row per block instead of one per tile.
 template <typename T, bool VEC, int G, int C, int B>
 __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
     typedef RowLoad<T, VEC> L;
-    enum { E = L::E };
+    enum { E = L::E, TPB = 256 / G, MERGE = (C * E <= 16) ? 1 : 0 };
     __shared__ uint64_t s_base[PX_MAX_SOURCES];
+    __shared__ double s_part[MERGE ? TPB * G * C * E : 1];
     for (int i = threadIdx.x; i < a.n_workers; i += 256) s_base[i] = a.words[a.n_workers + i];
     __syncthreads();
 
     const int gl = threadIdx.x % G;
-    const int64_t tile = (int64_t) blockIdx.x * (256 / G) + threadIdx.x / G;
-    if (tile >= a.n_tiles) return;
-    const uint32_t ts = a.tile_s[tile];
-    const int64_t s = (int64_t) (ts & TILE_POS_MASK);
-    bool started = (ts & TILE_STARTS_AT_HEAD) != 0u;
-    int64_t e = a.m;
-    bool next_is_head = true;
-    if (tile + 1 < a.n_tiles) {
-        const uint32_t tn = a.tile_s[tile + 1];
-        e = (int64_t) (tn & TILE_POS_MASK);
-        next_is_head = (tn & TILE_STARTS_AT_HEAD) != 0u;
+    const int gj = threadIdx.x / G;                               // tile inside the block
+    const int64_t tile = (int64_t) blockIdx.x * TPB + gj;
+    const bool active = tile < a.n_tiles;
+    int64_t s = 0, e = 0;
+    bool started = false, next_is_head = true, pure = false;
+    uint32_t u = 0;
+    if (active) {
+        const uint4 ti = a.tile_info[tile];
+        s = (int64_t) ti.x;
+        started = (ti.y & TILE_STARTS_AT_HEAD) != 0u;
+        pure = (ti.y & TILE_HAS_HEAD) == 0u;
+        u = ti.z;
+        e = a.m;
+        if (tile + 1 < a.n_tiles) {
+            const uint4 tn = a.tile_info[tile + 1];
+            e = (int64_t) tn.x;
+            next_is_head = (tn.y & TILE_STARTS_AT_HEAD) != 0u;
+        }
     }
+    // the last tile of the block also vouches for the run going on into the next block
+    const bool inside = active && pure && (gj < TPB - 1 || !next_is_head);
+    const bool merged = MERGE ? (__syncthreads_and(inside ? 1 : 0) != 0) : false;
 
     int piece[C];
     bool live[C];
@@ -377,14 +416,26 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
     }
     const uint32_t local_mask = (a.local_bits >= 32) ? 0xffffffffu : ((1u << a.local_bits) - 1u);
 
-    double acc[C][E];
+    seg_acc_t acc[C][E];
 #pragma unroll
     for (int c = 0; c < C; ++c)
 #pragma unroll
-        for (int x = 0; x < E; ++x) acc[c][x] = 0.0;
+        for (int x = 0; x < E; ++x) acc[c][x] = (seg_acc_t) 0;
 
-    uint32_t u = a.tile_u[tile];
-    uint32_t cur = key_of(a.sorted[s]);
+    auto store_partial = [&](double* dst) {
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const size_t sc = (size_t) blockIdx.y * C + c;
+            if (VEC) {
+#pragma unroll
+                for (int x = 0; x < E; x += 2)
+                    *(double2*) (dst + ((sc * (E / 2) + x / 2) * G + gl) * 2) =
+                        make_double2((double) acc[c][x], (double) acc[c][x + 1]);
+            } else {
+                dst[sc * G + gl] = (double) acc[c][0];
+            }
+        }
+    };
 
     auto flush = [&](bool ended) {
         if (started && ended) {
@@ -395,96 +446,147 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
                     if (VEC) {
 #pragma unroll
                         for (int x = 0; x < E; x += 4) {
-                            float4 o = make_float4((float) (acc[c][x] * a.scale), (float) (acc[c][x + 1] * a.scale),
-                                                   (float) (acc[c][x + 2] * a.scale), (float) (acc[c][x + 3] * a.scale));
+                            float4 o = make_float4((float) ((double) acc[c][x] * a.scale), (float) ((double) acc[c][x + 1] * a.scale),
+                                                   (float) ((double) acc[c][x + 2] * a.scale), (float) ((double) acc[c][x + 3] * a.scale));
                             *(float4*) (dst + (size_t) piece[c] * E + x) = o;
                         }
                     } else {
-                        dst[piece[c]] = (float) (acc[c][0] * a.scale);
+                        dst[piece[c]] = (float) ((double) acc[c][0] * a.scale);
                     }
                 }
         } else {
-            double* dst = (started ? a.plast : a.pfirst) + (size_t) tile * a.pstride;
-#pragma unroll
-            for (int c = 0; c < C; ++c) {
-                const size_t sc = (size_t) blockIdx.y * C + c;
-                if (VEC) {
-#pragma unroll
-                    for (int x = 0; x < E; x += 2)
-                        *(double2*) (dst + ((sc * (E / 2) + x / 2) * G + gl) * 2) = make_double2(acc[c][x], acc[c][x + 1]);
-                } else {
-                    dst[sc * G + gl] = acc[c][0];
-                }
-            }
+            store_partial((started ? a.plast : a.pfirst) + (size_t) tile * a.pstride);
             if (started && gl == 0 && blockIdx.y == 0) {
-                uint32_t slot = atomicAdd(a.span_count, 1u);
-                a.span_list[slot] = u;
+                // this tile holds the head of a run that goes on: record where the run ends
+                const uint32_t last_row = a.run_start[u + 1] - 1u;
+                uint32_t last_tile = last_row / (uint32_t) a.tile_rows;
+                if (a.tile_info[last_tile].x > last_row) --last_tile;
+                const bool is_long = last_tile - (uint32_t) tile > (uint32_t) SPAN_LONG_TILES;
+                const uint32_t slot = atomicAdd(a.counters + (is_long ? 0 : 1), 1u);
+                (is_long ? a.span_long : a.span_short)[slot] = make_uint4(u, (uint32_t) tile, last_tile, 0u);
             }
         }
 #pragma unroll
         for (int c = 0; c < C; ++c)
 #pragma unroll
-            for (int x = 0; x < E; ++x) acc[c][x] = 0.0;
+            for (int x = 0; x < E; ++x) acc[c][x] = (seg_acc_t) 0;
     };
 
-    for (int64_t r = s; r < e; r += B) {
-        uint64_t w[B];
-        typename L::Raw raw[B][C];
+    if (active) {
+        uint32_t cur = key_of(a.sorted[s]);
+        for (int64_t r = s; r < e; r += B) {
+            uint64_t w[B];
+            typename L::Raw raw[B][C];
 #pragma unroll
-        for (int j = 0; j < B; ++j) w[j] = (r + j < e) ? a.sorted[r + j] : 0ull;
+            for (int j = 0; j < B; ++j) w[j] = (r + j < e) ? a.sorted[r + j] : 0ull;
 #pragma unroll
-        for (int j = 0; j < B; ++j) {
-            if (r + j < e) {
-                const uint32_t payload = (uint32_t) w[j];
-                const uint32_t worker = (a.local_bits >= 32) ? 0u : (payload >> a.local_bits);
-                const char* row = (const char*) s_base[worker] + (size_t) (payload & local_mask) * a.row_bytes;
+            for (int j = 0; j < B; ++j) {
+                if (r + j < e) {
+                    const uint32_t payload = (uint32_t) w[j];
+                    const uint32_t worker = (a.local_bits >= 32) ? 0u : (payload >> a.local_bits);
+                    const char* row = (const char*) s_base[worker] + (size_t) (payload & local_mask) * a.row_bytes;
 #pragma unroll
-                for (int c = 0; c < C; ++c)
-                    if (live[c]) raw[j][c] = L::load(row + (size_t) piece[c] * (E * sizeof(T)));
+                    for (int c = 0; c < C; ++c)
+                        if (live[c]) raw[j][c] = L::load(row + (size_t) piece[c] * (E * sizeof(T)));
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                if (r + j < e) {
+                    const uint32_t k = key_of(w[j]);
+                    if (k != cur) {
+                        flush(true);
+                        ++u;
+                        cur = k;
+                        started = true;
+                    }
+#pragma unroll
+                    for (int c = 0; c < C; ++c)
+                        if (live[c]) L::add(acc[c], raw[j][c]);
+                }
             }
         }
+        if (!merged) flush(next_is_head);
+    }
+
+    if (MERGE && merged) {                                    // uniform over the block
+        // every tile of the block is a continuation of one run with no head inside: add in tile order
 #pragma unroll
-        for (int j = 0; j < B; ++j) {
-            if (r + j < e) {
-                const uint32_t k = key_of(w[j]);
-                if (k != cur) {
-                    flush(true);
-                    ++u;
-                    cur = k;
-                    started = true;
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int x = 0; x < E; ++x) s_part[((gj * C + c) * E + x) * G + gl] = (double) acc[c][x];
+        __syncthreads();
+        if (gj == 0) {
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+#pragma unroll
+                for (int x = 0; x < E; ++x) {
+                    double t = s_part[((0 * C + c) * E + x) * G + gl];
+                    for (int j = 1; j < TPB; ++j) t += s_part[((j * C + c) * E + x) * G + gl];
+                    acc[c][x] = (seg_acc_t) t;
                 }
-#pragma unroll
-                for (int c = 0; c < C; ++c)
-                    if (live[c]) L::add(acc[c], raw[j][c]);
-            }
+            store_partial(a.pfirst + (size_t) tile * a.pstride);
         }
     }
-    flush(next_is_head);
 }
 
 // -------------------------------------------------------------------- fix-up
-// A run split over tiles a..b left partial rows plast[a], pfirst[a+1..b].  One block of 16
-// waves per split run and 64-double slab of the (lane-interleaved) partial row: wave w adds
-// parts w, w+16, ... in double, the 16 sums are added in wave order, the result is rounded once
-// and written to the column the slot stands for.
+// A run split over tiles first..last left partial rows plast[first], then pfirst[t] for the tiles
+// after it -- except that a block of tiles_per_block tiles lying strictly inside the run left a
+// single row, at its first tile.  Rows are added in double, rounded once and written to the
+// column each slot of the lane-interleaved partial row stands for.
+//   long runs   one workgroup of 16 waves per run and 64-slot slab: wave w adds parts w, w+16, ...,
+//               the 16 sums are added in wave order
+//   other runs  one wave per run and slab
 enum { FIX_SPLITS = 16 };
 
 struct FixupArgs {
-    const uint32_t* tile_s;
-    const uint32_t* span_list;
-    const uint32_t* span_count;
+    const uint4* span_long;
+    const uint4* span_short;
+    const uint32_t* counters;
     const uint32_t* run_start;
     const double* pfirst;
     const double* plast;
     float* out_rows;
     int32_t* out_run_len;
     const int64_t* num_unique;
-    int64_t m;
     int64_t dim;
     int64_t pstride;
-    int tile_rows;
+    int tiles_per_block;          // 0: the segsum kernel never merges
     int G, C, E, pieces;
     float scale;
+};
+
+// The q-th partial row (q = 0 .. parts-1) of a run over tiles first..last.
+struct PartList {
+    uint32_t first, heads, merged, g0, g1, tpb, parts;
+    __device__ PartList(uint32_t first_tile, uint32_t last_tile, uint32_t tiles_per_block) {
+        first = first_tile;
+        tpb = tiles_per_block;
+        heads = last_tile - first_tile;        // no merged block: every later tile is its own part
+        merged = 0;
+        g0 = g1 = 0;
+        if (tpb > 0) {
+            const uint32_t lo = (first_tile + 1u + tpb - 1u) / tpb;      // first block starting after `first`
+            const uint32_t hi = last_tile / tpb;                         // blocks below hi end before `last`
+            if (lo < hi) {
+                g0 = lo;
+                g1 = hi;
+                heads = g0 * tpb - (first_tile + 1u);
+                merged = g1 - g0;
+            }
+        }
+        const uint32_t tail = merged ? last_tile - g1 * tpb + 1u : 0u;
+        parts = 1u + heads + merged + tail;
+    }
+    __device__ const double* row(uint32_t q, const double* pfirst, const double* plast, int64_t pstride) const {
+        if (q == 0) return plast + (size_t) first * pstride;
+        uint32_t t;
+        if (q <= heads) t = first + q;
+        else if (q <= heads + merged) t = (g0 + (q - heads - 1u)) * tpb;
+        else t = g1 * tpb + (q - heads - merged - 1u);
+        return pfirst + (size_t) t * pstride;
+    }
 };
 
 __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
@@ -501,34 +603,21 @@ __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
     const int64_t col = piece * a.E + (t % halves) * pair + pe % pair;
     const bool live = pe < a.pstride && piece < a.pieces;
 
-    const uint32_t count = a.span_count[0];
-    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
-        const uint32_t u = a.span_list[i];
-        const uint32_t end = a.run_start[u + 1];
-        const uint32_t first_tile = a.run_start[u] / (uint32_t) a.tile_rows;
-        uint32_t last_tile = (end - 1u) / (uint32_t) a.tile_rows;       // tile holding the run's last row
-        if ((a.tile_s[last_tile] & TILE_POS_MASK) > end - 1u) --last_tile;
-        const uint32_t parts = last_tile - first_tile + 1u;
+    const uint32_t n_long = a.counters[0], n_short = a.counters[1];
+    for (uint32_t i = blockIdx.x; i < n_long; i += gridDim.x) {
+        const uint4 rec = a.span_long[i];
+        const PartList pl(rec.y, rec.z, (uint32_t) a.tiles_per_block);
         double acc = 0.0;
         if (live) {
             uint32_t q = split;
-            for (; q + 7 * FIX_SPLITS < parts; q += 8 * FIX_SPLITS) {
+            for (; q + 7 * FIX_SPLITS < pl.parts; q += 8 * FIX_SPLITS) {
                 double v[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t qq = q + j * FIX_SPLITS;
-                    const double* src = (qq == 0) ? a.plast + (size_t) first_tile * a.pstride
-                                                  : a.pfirst + (size_t) (first_tile + qq) * a.pstride;
-                    v[j] = src[pe];
-                }
+                for (int j = 0; j < 8; ++j) v[j] = pl.row(q + j * FIX_SPLITS, a.pfirst, a.plast, a.pstride)[pe];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc += v[j];
             }
-            for (; q < parts; q += FIX_SPLITS) {
-                const double* src = (q == 0) ? a.plast + (size_t) first_tile * a.pstride
-                                             : a.pfirst + (size_t) (first_tile + q) * a.pstride;
-                acc += src[pe];
-            }
+            for (; q < pl.parts; q += FIX_SPLITS) acc += pl.row(q, a.pfirst, a.plast, a.pstride)[pe];
         }
         s_red[split][lane] = acc;
         __syncthreads();
@@ -536,9 +625,26 @@ __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
             double tsum = 0.0;
 #pragma unroll
             for (int w = 0; w < FIX_SPLITS; ++w) tsum += s_red[w][lane];
-            a.out_rows[(size_t) u * a.dim + col] = (float) (tsum * a.scale);
+            a.out_rows[(size_t) rec.x * a.dim + col] = (float) (tsum * a.scale);
         }
         __syncthreads();
+    }
+    for (uint32_t i = blockIdx.x * FIX_SPLITS + split; i < n_short; i += gridDim.x * FIX_SPLITS) {
+        const uint4 rec = a.span_short[i];
+        const PartList pl(rec.y, rec.z, (uint32_t) a.tiles_per_block);
+        if (live) {
+            double acc = 0.0;
+            uint32_t q = 0;
+            for (; q + 3 < pl.parts; q += 4) {
+                double v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = pl.row(q + j, a.pfirst, a.plast, a.pstride)[pe];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc += v[j];
+            }
+            for (; q < pl.parts; ++q) acc += pl.row(q, a.pfirst, a.plast, a.pstride)[pe];
+            a.out_rows[(size_t) rec.x * a.dim + col] = (float) (acc * a.scale);
+        }
     }
     if (a.out_run_len != nullptr && blockIdx.y == 0) {
         const int64_t n = a.num_unique[0];
@@ -560,11 +666,11 @@ int bits_for(uint64_t max_value) {   // bits needed to write max_value
 template <typename T, bool VEC>
 void launch_segsum(const SegsumArgs& a, const RowShape& sh, hipStream_t stream) {
     const dim3 grid((unsigned) ((a.n_tiles + (256 / sh.G) - 1) / (256 / sh.G)), (unsigned) sh.slabs, 1);
-    if (sh.G == 16) k_segsum<T, VEC, 16, 1, 8><<<grid, 256, 0, stream>>>(a);
-    else if (sh.G == 32) k_segsum<T, VEC, 32, 1, 8><<<grid, 256, 0, stream>>>(a);
-    else if (sh.C == 1) k_segsum<T, VEC, 64, 1, 8><<<grid, 256, 0, stream>>>(a);
-    else if (sh.C == 2) k_segsum<T, VEC, 64, 2, 8><<<grid, 256, 0, stream>>>(a);
-    else k_segsum<T, VEC, 64, 4, 4><<<grid, 256, 0, stream>>>(a);
+    if (sh.G == 16) k_segsum<T, VEC, 16, 1, PX_SEG_ROWS><<<grid, 256, 0, stream>>>(a);
+    else if (sh.G == 32) k_segsum<T, VEC, 32, 1, PX_SEG_ROWS><<<grid, 256, 0, stream>>>(a);
+    else if (sh.C == 1) k_segsum<T, VEC, 64, 1, PX_SEG_ROWS><<<grid, 256, 0, stream>>>(a);
+    else if (sh.C == 2) k_segsum<T, VEC, 64, 2, PX_SEG_ROWS><<<grid, 256, 0, stream>>>(a);
+    else k_segsum<T, VEC, 64, 4, PX_SEG_ROWS_WIDE><<<grid, 256, 0, stream>>>(a);
 }
 
 }  // namespace
@@ -657,18 +763,19 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
     const int n_hblocks = (int) ((m + PX_SORT_TILE - 1) / PX_SORT_TILE);
     k_heads_count<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount);
     k_heads_emit<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount, tile_rows, out_ids, sc.run_start,
-                                                sc.tile_s, sc.tile_u, out_num_unique, ctx->d_flags);
+                                                sc.tile_info, out_num_unique, ctx->d_flags);
 
     const RowShape sh = row_shape(dim, (int) es, vec);
     SegsumArgs a;
     a.sorted = sorted;
     a.words = ctx->d_words;
-    a.tile_s = sc.tile_s;
-    a.tile_u = sc.tile_u;
+    a.tile_info = sc.tile_info;
+    a.run_start = sc.run_start;
     a.pfirst = sc.pfirst;
     a.plast = sc.plast;
-    a.span_list = sc.span_list;
-    a.span_count = sc.counters;
+    a.span_long = sc.span_long;
+    a.span_short = sc.span_short;
+    a.counters = sc.counters;
     a.out_rows = out_rows;
     a.m = m;
     a.n_tiles = n_tiles;
@@ -677,6 +784,7 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
     a.pstride = sh.pstride;
     a.n_workers = n_workers;
     a.local_bits = local_bits;
+    a.tile_rows = tile_rows;
     a.pieces = sh.pieces;
     a.scale = scale;
     if (vec) {
@@ -687,19 +795,18 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
         else launch_segsum<uint16_t, false>(a, sh, stream);
     }
     FixupArgs f;
-    f.tile_s = sc.tile_s;
-    f.span_list = sc.span_list;
-    f.span_count = sc.counters;
+    f.span_long = sc.span_long;
+    f.span_short = sc.span_short;
+    f.counters = sc.counters;
     f.run_start = sc.run_start;
     f.pfirst = sc.pfirst;
     f.plast = sc.plast;
     f.out_rows = out_rows;
     f.out_run_len = out_run_len;
     f.num_unique = out_num_unique;
-    f.m = m;
     f.dim = dim;
     f.pstride = sh.pstride;
-    f.tile_rows = tile_rows;
+    f.tiles_per_block = (sh.C * sh.E <= 16) ? 256 / sh.G : 0;      // the segsum kernel's MERGE rule
     f.G = sh.G;
     f.C = sh.C;
     f.E = sh.E;
