@@ -37,6 +37,36 @@ template <> struct Piece<false> {
     enum { E = 1 };
 };
 
+typedef float apply_v4f __attribute__((ext_vector_type(4)));
+// The aggregated gradient row is read exactly once.
+__device__ __forceinline__ float4 load_grad(const float4* p) {
+#ifdef PX_APPLY_NONTEMPORAL
+    apply_v4f v = __builtin_nontemporal_load((const apply_v4f*) p);
+    return make_float4(v.x, v.y, v.z, v.w);
+#else
+    return *p;
+#endif
+}
+__device__ __forceinline__ float load_grad(const float* p) { return *p; }
+__device__ __forceinline__ float4 load_state(const float4* p) {
+#ifdef PX_APPLY_NT_STATE_LOAD
+    apply_v4f v = __builtin_nontemporal_load((const apply_v4f*) p);
+    return make_float4(v.x, v.y, v.z, v.w);
+#else
+    return *p;
+#endif
+}
+__device__ __forceinline__ float load_state(const float* p) { return *p; }
+__device__ __forceinline__ void store_state(float4* p, float4 v) {
+#ifdef PX_APPLY_NT_STATE_STORE
+    apply_v4f t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, (apply_v4f*) p);
+#else
+    *p = v;
+#endif
+}
+__device__ __forceinline__ void store_state(float* p, float v) { *p = v; }
+
 __device__ __forceinline__ void sgd(float& w, float g, float lr) { w = w - lr * g; }
 __device__ __forceinline__ void adagrad(float& w, float& a, float g, float lr, float eps) {
     a = a + g * g;
@@ -78,9 +108,9 @@ __global__ __launch_bounds__(256) void k_apply(ApplyArgs p) {
             for (int c = 0; c < C; ++c) {
                 const int pc = p0 + c * G + gl;
                 if (pc < p.pieces) {
-                    gv[c] = g[pc];
-                    wv[c] = w[pc];
-                    if (ADAGRAD) av[c] = a[pc];
+                    gv[c] = load_grad(g + pc);
+                    wv[c] = load_state(w + pc);
+                    if (ADAGRAD) av[c] = load_state(a + pc);
                 }
             }
 #pragma unroll
@@ -95,8 +125,8 @@ __global__ __launch_bounds__(256) void k_apply(ApplyArgs p) {
                         if (ADAGRAD) adagrad(wf[x], af[x], gf[x], p.lr, p.eps);
                         else sgd(wf[x], gf[x], p.lr);
                     }
-                    w[pc] = wv[c];
-                    if (ADAGRAD) a[pc] = av[c];
+                    store_state(w + pc, wv[c]);
+                    if (ADAGRAD) store_state(a + pc, av[c]);
                 }
             }
         }

@@ -299,12 +299,33 @@ __global__ void k_write_zero_count(int64_t* out_num_unique) {
 #endif
 typedef PX_SEG_ACC seg_acc_t;
 
+typedef uint32_t seg_v4u __attribute__((ext_vector_type(4)));
+// Value rows are read exactly once.
+__device__ __forceinline__ uint4 seg_load16(const char* p) {
+#ifdef PX_SEG_TEMPORAL
+    return *(const uint4*) p;
+#else
+    seg_v4u v = __builtin_nontemporal_load((const seg_v4u*) p);     // stream past the caches
+    return make_uint4(v.x, v.y, v.z, v.w);
+#endif
+}
+
+typedef float seg_v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void seg_store16(float* p, float4 v) {
+#ifdef PX_SEG_NT_STORE
+    seg_v4f t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, (seg_v4f*) p);
+#else
+    *(float4*) p = v;
+#endif
+}
+
 template <typename T, bool VEC> struct RowLoad;
 
 template <> struct RowLoad<float, true> {
     typedef uint4 Raw;
     enum { E = 4 };
-    static __device__ __forceinline__ Raw load(const char* p) { return *(const uint4*) p; }
+    static __device__ __forceinline__ Raw load(const char* p) { return seg_load16(p); }
     static __device__ __forceinline__ void add(seg_acc_t* acc, const Raw& r) {
         acc[0] += (seg_acc_t) __uint_as_float(r.x);
         acc[1] += (seg_acc_t) __uint_as_float(r.y);
@@ -322,7 +343,7 @@ template <> struct RowLoad<float, false> {
 template <> struct RowLoad<uint16_t, true> {
     typedef uint4 Raw;
     enum { E = 8 };
-    static __device__ __forceinline__ Raw load(const char* p) { return *(const uint4*) p; }
+    static __device__ __forceinline__ Raw load(const char* p) { return seg_load16(p); }
     static __device__ __forceinline__ void add(seg_acc_t* acc, const Raw& r) {
         acc[0] += (seg_acc_t) __uint_as_float(r.x << 16);
         acc[1] += (seg_acc_t) __uint_as_float(r.x & 0xffff0000u);
@@ -448,7 +469,7 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
                         for (int x = 0; x < E; x += 4) {
                             float4 o = make_float4((float) ((double) acc[c][x] * a.scale), (float) ((double) acc[c][x + 1] * a.scale),
                                                    (float) ((double) acc[c][x + 2] * a.scale), (float) ((double) acc[c][x + 3] * a.scale));
-                            *(float4*) (dst + (size_t) piece[c] * E + x) = o;
+                            seg_store16(dst + (size_t) piece[c] * E + x, o);
                         }
                     } else {
                         dst[piece[c]] = (float) ((double) acc[c][0] * a.scale);
