@@ -3,12 +3,10 @@
 // Parallax Fig. 3 / Sec. 3.2: the workers' (indices, values) arrays are
 // concatenated and values carrying the same index are accumulated.  On the GPU:
 //   1. pack    every input row becomes one 64-bit word  id << 32 | worker << LB | local row
-//              (the same kernel counts the digits of every pass and clears the passes' state)
 //   2. sort    stable least-significant-digit radix sort of the words on the id bits only
-//              (ceil(log2 vocab) bits, 8 per pass, one kernel per pass); value rows never move
-//   3. heads   a row is a run head if its id differs from its predecessor's; ranking the
-//              heads (one kernel, block totals chained by look-back) yields U, the distinct
-//              ids and every run's start
+//              (ceil(log2 vocab) bits, 8 per pass); value rows never move
+//   3. heads   a row is a run head if its id differs from its predecessor's; counting and
+//              ranking the heads yields U, the distinct ids and every run's start
 //   4. segsum  the sorted order is cut into windows of T rows; tile t starts at the first head
 //              in the leading quarter of window t (else at the window's own border) and ends
 //              where tile t+1 starts, so the short runs that dominate never straddle two tiles
@@ -17,9 +15,8 @@
 //              double.  Whole runs are rounded and written at once; a split run leaves one
 //              double-precision partial row per tile
 //   5. fixup   each split run adds up its partial rows, rounds once, writes its row
-// Workgroups wait on each other only inside the sort passes and the head ranking (bounded
-// look-back, see px_radix.h); global atomics only count digits, hand out tile tickets and append
-// to the lists of split runs, so every output is deterministic.
+// Nothing waits on another workgroup and global atomics only append to the list of split
+// runs, so the sums are deterministic.
 #include "px_radix.h"
 
 namespace {
@@ -91,25 +88,17 @@ enum : uint32_t {
 // A split run: x = run index, y = tile holding its first row, z = tile holding its last row.
 enum { SPAN_LONG_TILES = 32 };  // runs over more tiles than this get a whole workgroup in the fix-up
 
-enum {
-    MAX_PASSES = 4,                 // 32 id bits, 8 per pass
-    CNT_SPAN_LONG = 0,              // length of span_long
-    CNT_SPAN_SHORT = 1,             // length of span_short
-    CNT_TICKET = 16,                // [MAX_PASSES] tile tickets of the sort passes, then one for the heads
-    CNT_DIGITS = 256,               // [MAX_PASSES][256] items per digit of every pass
-    CNT_WORDS = CNT_DIGITS + MAX_PASSES * PX_RADIX
-};
-
 struct Scratch {
     uint64_t* keys_a;
     uint64_t* keys_b;
-    uint64_t* sweep_state; // [MAX_PASSES][n_sort_tiles][256] look-back words of the sort passes
-    uint64_t* heads_state; // [n_sort_tiles] look-back words of the head ranking
+    uint32_t* hist;        // [PX_SORT_MAX_BLOCKS][256]
+    uint32_t* totals;      // [256] items per digit
+    uint32_t* hcount;      // heads per 2048-row block
     uint32_t* run_start;   // [M + 1]
     uint4* tile_info;      // [n_tiles] first row, flags, run index of the first row
     uint4* span_long;      // [n_tiles] split runs over more than SPAN_LONG_TILES tiles
     uint4* span_short;     // [n_tiles] the other split runs
-    uint32_t* counters;    // see CNT_* below
+    uint32_t* counters;    // [0] = length of span_long, [1] = length of span_short
     double* pfirst;        // [n_tiles][pstride] partial of the run entering a tile
     double* plast;         // [n_tiles][pstride] partial of the run leaving a tile
     size_t bytes;
@@ -119,7 +108,7 @@ inline Scratch carve(void* base, int64_t m, int64_t dim) {
     Scratch s;
     const int t = tile_rows_for(m);
     const size_t n_tiles = (size_t) ((m + t - 1) / t);
-    const size_t n_sort_tiles = (size_t) px_sort_tiles(m);
+    const size_t n_hblocks = (size_t) ((m + PX_SORT_TILE - 1) / PX_SORT_TILE);
     const size_t pstride = (size_t) max_partial_stride(dim);
     size_t off = 0;
     char* b = (char*) base;
@@ -130,13 +119,14 @@ inline Scratch carve(void* base, int64_t m, int64_t dim) {
     };
     s.keys_a = (uint64_t*) take((size_t) m * 8);
     s.keys_b = (uint64_t*) take((size_t) m * 8);
-    s.sweep_state = (uint64_t*) take((size_t) MAX_PASSES * n_sort_tiles * PX_RADIX * 8);
-    s.heads_state = (uint64_t*) take(n_sort_tiles * 8);
+    s.hist = (uint32_t*) take((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX * 4);
+    s.totals = (uint32_t*) take(PX_RADIX * 4);
+    s.hcount = (uint32_t*) take((n_hblocks + 1) * 4);
     s.run_start = (uint32_t*) take(((size_t) m + 1) * 4);
     s.tile_info = (uint4*) take((n_tiles + 1) * 16);
     s.span_long = (uint4*) take((n_tiles + 1) * 16);
     s.span_short = (uint4*) take((n_tiles + 1) * 16);
-    s.counters = (uint32_t*) take(CNT_WORDS * 4);
+    s.counters = (uint32_t*) take(64 * 4);
     s.pfirst = (double*) take(n_tiles * pstride * 8);
     s.plast = (double*) take(n_tiles * pstride * 8);
     s.bytes = off;
@@ -147,68 +137,38 @@ __device__ __forceinline__ uint32_t key_of(uint64_t w) { return (uint32_t) (w >>
 
 // ---------------------------------------------------------------------- pack
 
-// One block per sort tile: packs its rows, counts the digits of every pass (LDS, then one global
-// atomic per digit and block) and clears the look-back words its tile will use later.
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(const uint64_t* __restrict__ words,
                                                           int n_workers, int64_t m, int64_t vocab,
-                                                          int local_bits, int passes,
-                                                          uint64_t* __restrict__ keys,
-                                                          uint32_t* __restrict__ counters,
-                                                          uint64_t* __restrict__ sweep_state,
-                                                          uint64_t* __restrict__ heads_state,
-                                                          int64_t n_sort_tiles,
+                                                          int local_bits, uint64_t* __restrict__ keys,
+                                                          uint32_t* __restrict__ hist, int64_t chunk,
                                                           uint32_t* __restrict__ flags) {
     __shared__ uint32_t s_prefix[PX_MAX_SOURCES + 1];
-    __shared__ uint32_t s_hist[MAX_PASSES][PX_RADIX];
+    __shared__ uint32_t s_hist[PX_RADIX];
     const int tid = threadIdx.x;
     for (int i = tid; i <= n_workers; i += PX_SORT_THREADS) s_prefix[i] = (uint32_t) words[2 * n_workers + i];
-    for (int p = 0; p < MAX_PASSES; ++p) s_hist[p][tid] = 0u;
-    for (int p = 0; p < passes; ++p)
-        sweep_state[((size_t) p * n_sort_tiles + blockIdx.x) * PX_RADIX + tid] = 0ull;
-    if (tid == 0) heads_state[blockIdx.x] = 0ull;
+    s_hist[tid] = 0u;
     __syncthreads();
     const int64_t* const* idx = (const int64_t* const*) words;
-    const int64_t begin = (int64_t) blockIdx.x * PX_SORT_TILE;
-
-    int worker[PX_SORT_ITEMS];
-    uint32_t local[PX_SORT_ITEMS];
-    int64_t id[PX_SORT_ITEMS];
-#pragma unroll
-    for (int j = 0; j < PX_SORT_ITEMS; ++j) {
-        const int64_t p = begin + j * PX_SORT_THREADS + tid;
+    const int64_t begin = (int64_t) blockIdx.x * chunk;
+    int64_t end = begin + chunk;
+    if (end > m) end = m;
+    for (int64_t p = begin + tid; p < end; p += PX_SORT_THREADS) {
         int lo = 0, hi = n_workers;                 // s_prefix[lo] <= p < s_prefix[hi]
-        if (p < m) {
-            while (hi - lo > 1) {
-                int mid = (lo + hi) >> 1;
-                if ((int64_t) s_prefix[mid] <= p) lo = mid; else hi = mid;
-            }
-            local[j] = (uint32_t) (p - (int64_t) s_prefix[lo]);
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if ((int64_t) s_prefix[mid] <= p) lo = mid; else hi = mid;
         }
-        worker[j] = lo;
-    }
-#pragma unroll
-    for (int j = 0; j < PX_SORT_ITEMS; ++j) {
-        const int64_t p = begin + j * PX_SORT_THREADS + tid;
-        if (p < m) id[j] = idx[worker[j]][local[j]];
-    }
-#pragma unroll
-    for (int j = 0; j < PX_SORT_ITEMS; ++j) {
-        const int64_t p = begin + j * PX_SORT_THREADS + tid;
-        if (p < m) {
-            int64_t v = id[j];
-            if (v < 0 || v >= vocab) {
-                atomicOr(flags, (uint32_t) PXF_BAD_ID);
-                v = 0;
-            }
-            keys[p] = ((uint64_t) (uint32_t) v << 32) | (uint64_t) (((uint32_t) worker[j] << local_bits) | local[j]);
-            for (int q = 0; q < passes; ++q) atomicAdd(&s_hist[q][((uint32_t) v >> (8 * q)) & 255u], 1u);
+        const uint32_t local = (uint32_t) (p - (int64_t) s_prefix[lo]);
+        int64_t id = idx[lo][local];
+        if (id < 0 || id >= vocab) {
+            atomicOr(flags, (uint32_t) PXF_BAD_ID);
+            id = 0;
         }
+        keys[p] = ((uint64_t) (uint32_t) id << 32) | (uint64_t) (((uint32_t) lo << local_bits) | local);
+        atomicAdd(&s_hist[(uint32_t) id & 255u], 1u);
     }
     __syncthreads();
-    for (int q = 0; q < passes; ++q) {
-        const uint32_t c = s_hist[q][tid];
-        if (c) atomicAdd(counters + CNT_DIGITS + q * PX_RADIX + tid, c);
-    }
+    hist[(size_t) blockIdx.x * PX_RADIX + tid] = s_hist[tid];
 }
 
 struct SortWords {
@@ -220,25 +180,42 @@ struct SortWords {
     __device__ int64_t count() const { return n; }
     __device__ Item load(int64_t i) const { return in[i]; }
     __device__ uint32_t digit(Item v, int64_t) const { return (uint32_t) (v >> (32 + shift)) & 255u; }
+    __device__ void note(int64_t, uint32_t) const {}
     __device__ void store(uint32_t dst, Item v) const { out[dst] = v; }
     __device__ void publish(int, uint32_t, uint32_t) const {}
 };
 
 // --------------------------------------------------------------------- heads
 
+__global__ __launch_bounds__(256) void k_heads_count(const uint64_t* __restrict__ sorted, int64_t m,
+                                                     uint32_t* __restrict__ hcount) {
+    __shared__ uint32_t s_cnt;
+    if (threadIdx.x == 0) s_cnt = 0u;
+    __syncthreads();
+    const int64_t base = (int64_t) blockIdx.x * PX_SORT_TILE;
+    uint32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < PX_SORT_ITEMS; ++j) {
+        const int64_t i = base + j * 256 + threadIdx.x;
+        if (i < m) c += (i == 0 || key_of(sorted[i]) != key_of(sorted[i - 1])) ? 1u : 0u;
+    }
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o);
+    if (pxr::lane_id() == 0) atomicAdd(&s_cnt, c);
+    __syncthreads();
+    if (threadIdx.x == 0) hcount[blockIdx.x] = s_cnt;
+}
+
 // Ranks the heads: distinct ids, run starts, U; and for every window of tile_rows rows the tile
 // that starts there: its first row (the first head in the leading part of the window, else the
 // window's own first row), the run that row belongs to, and whether the window holds any head.
-// One block per 2048 rows, numbered by ticket; the heads in earlier blocks come from look-back.
-__global__ __launch_bounds__(256) void k_heads(const uint64_t* __restrict__ sorted, int64_t m, int tile_rows,
-                                               int64_t* __restrict__ out_ids, uint32_t* __restrict__ run_start,
-                                               uint4* __restrict__ tile_info,
-                                               int64_t* __restrict__ out_num_unique,
-                                               uint64_t* __restrict__ state, uint32_t* __restrict__ ticket,
-                                               uint32_t* __restrict__ flags) {
+__global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__ sorted, int64_t m,
+                                                    const uint32_t* __restrict__ hcount, int tile_rows,
+                                                    int64_t* __restrict__ out_ids,
+                                                    uint32_t* __restrict__ run_start,
+                                                    uint4* __restrict__ tile_info,
+                                                    int64_t* __restrict__ out_num_unique,
+                                                    const uint32_t* __restrict__ flags) {
     __shared__ uint32_t s_wave[4];
-    __shared__ uint32_t s_block;
-    __shared__ uint32_t s_before;
     __shared__ uint32_t s_first[PX_SORT_TILE / 32];        // first aligning head of each window of this block
     __shared__ uint32_t s_any[PX_SORT_TILE / 32];          // does the window hold a head at all
     const int tid = threadIdx.x;
@@ -246,11 +223,13 @@ __global__ __launch_bounds__(256) void k_heads(const uint64_t* __restrict__ sort
         s_first[tid] = 0xffffffffu;
         s_any[tid] = 0u;
     }
-    if (tid == 0) s_block = atomicAdd(ticket, 1u);
-    __syncthreads();
-    const uint32_t block = s_block;
-    const uint32_t block_base = block * (uint32_t) PX_SORT_TILE;
-    if ((int64_t) block_base >= m) return;
+    // heads in all blocks before this one
+    uint32_t part = 0;
+    for (int b = tid; b < (int) blockIdx.x; b += 256) part += hcount[b];
+    uint32_t before;
+    pxr::block_exclusive_scan_256(part, s_wave, &before);
+
+    const uint32_t block_base = blockIdx.x * (uint32_t) PX_SORT_TILE;
     const int64_t base = (int64_t) block_base + (int64_t) tid * PX_SORT_ITEMS;
     // A head at a window's first row always starts the tile (align_rows >= 1), so every tile gets a start.
     const uint32_t align_rows = (uint32_t) tile_rows / PX_ALIGN_DIV > 0u ? (uint32_t) tile_rows / PX_ALIGN_DIV : 1u;
@@ -277,25 +256,7 @@ __global__ __launch_bounds__(256) void k_heads(const uint64_t* __restrict__ sort
         cnt += flag[j];
     }
     uint32_t block_total;
-    const uint32_t in_block = pxr::block_exclusive_scan_256(cnt, s_wave, &block_total);   // syncs
-    if (tid == 0) {
-        // heads in all blocks before this one
-        pxr::lb_store(state + block, pxr::LB_COUNT | (uint64_t) block_total);
-        uint32_t sum = 0;
-        const bool ok = pxr::look_back(state, 1, (int64_t) block, &sum);
-        pxr::lb_store(state + block, ok ? (pxr::LB_TOTAL | (uint64_t) (sum + block_total)) : (uint64_t) pxr::LB_POISON);
-        s_before = ok ? sum : 0xffffffffu;
-    }
-    __syncthreads();
-    const uint32_t before = s_before;
-    if (before == 0xffffffffu) {                    // a wait ran out: report, write nothing
-        if (tid == 0) {
-            atomicOr(flags, (uint32_t) PXF_INTERNAL);
-            out_num_unique[0] = 0;
-        }
-        return;
-    }
-    uint32_t rank = before + in_block;
+    uint32_t rank = before + pxr::block_exclusive_scan_256(cnt, s_wave, &block_total);   // syncs
 #pragma unroll
     for (int j = 0; j < PX_SORT_ITEMS; ++j) {
         const int64_t i = base + j;
@@ -314,10 +275,10 @@ __global__ __launch_bounds__(256) void k_heads(const uint64_t* __restrict__ sort
             }
         }
     }
-    if (tid == 0 && (int64_t) (block + 1) * PX_SORT_TILE >= m) {          // block holding the last row
+    if (tid == 0 && (int64_t) (blockIdx.x + 1) * PX_SORT_TILE >= m) {     // block holding the last row
         const uint32_t u = before + block_total;
         run_start[u] = (uint32_t) m;
-        out_num_unique[0] = (flags[0] & (PXF_BAD_ID | PXF_INTERNAL)) ? 0 : (int64_t) u;
+        out_num_unique[0] = (flags[0] & PXF_BAD_ID) ? 0 : (int64_t) u;
     }
 }
 
@@ -795,24 +756,23 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
         run += counts[w];
     }
     host_words[3 * n_workers] = (uint64_t) run;
-    // one launch for N <= 85 workers: [idx pointers | value pointers | row prefix]; clears the counters
-    px_status st = px_upload_words(ctx, ctx->d_words, host_words, 3 * n_workers + 1, sc.counters, CNT_WORDS, stream);
+    // one launch for N <= 85 workers: [idx pointers | value pointers | row prefix]
+    px_status st = px_upload_words(ctx, ctx->d_words, host_words, 3 * n_workers + 1, sc.counters, 64, stream);
     if (st != PX_OK) return st;
 
-    const int64_t n_sort_tiles = px_sort_tiles(m);
+    const px_sort_geom g = px_sort_geometry(m);
+    k_pack<<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, n_workers, m, vocab, local_bits,
+                                                       sc.keys_a, sc.hist, g.chunk, ctx->d_flags);
     int key_bits = bits_for((uint64_t) (vocab - 1));
     int passes = (key_bits + 7) / 8;
     if (passes < 1) passes = 1;
-    k_pack<<<(unsigned) n_sort_tiles, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, n_workers, m, vocab, local_bits, passes,
-                                                                   sc.keys_a, sc.counters, sc.sweep_state,
-                                                                   sc.heads_state, n_sort_tiles, ctx->d_flags);
     uint64_t* src = sc.keys_a;
     uint64_t* dst = sc.keys_b;
     for (int p = 0; p < passes; ++p) {
         SortWords pol{src, dst, m, 8 * p};
-        pxr::k_radix_sweep<SortWords><<<(unsigned) n_sort_tiles, PX_SORT_THREADS, 0, stream>>>(
-            pol, sc.counters + CNT_DIGITS + p * PX_RADIX, sc.sweep_state + (size_t) p * n_sort_tiles * PX_RADIX,
-            sc.counters + CNT_TICKET + p, ctx->d_flags);
+        if (p > 0) pxr::k_radix_hist<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, g.chunk);
+        pxr::k_radix_prefix<<<PX_RADIX / 4, 256, 0, stream>>>(sc.hist, g.n_blocks, sc.totals);
+        pxr::k_radix_scatter<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, sc.totals, g.chunk);
         uint64_t* t = src;
         src = dst;
         dst = t;
@@ -821,9 +781,10 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
 
     const int tile_rows = tile_rows_for(m);
     const int64_t n_tiles = (m + tile_rows - 1) / tile_rows;
-    k_heads<<<(unsigned) n_sort_tiles, 256, 0, stream>>>(sorted, m, tile_rows, out_ids, sc.run_start, sc.tile_info,
-                                                        out_num_unique, sc.heads_state,
-                                                        sc.counters + CNT_TICKET + MAX_PASSES, ctx->d_flags);
+    const int n_hblocks = (int) ((m + PX_SORT_TILE - 1) / PX_SORT_TILE);
+    k_heads_count<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount);
+    k_heads_emit<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount, tile_rows, out_ids, sc.run_start,
+                                                sc.tile_info, out_num_unique, ctx->d_flags);
 
     const RowShape sh = row_shape(dim, (int) es, vec);
     SegsumArgs a;
@@ -835,7 +796,7 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
     a.plast = sc.plast;
     a.span_long = sc.span_long;
     a.span_short = sc.span_short;
-    a.counters = sc.counters;      // CNT_SPAN_LONG, CNT_SPAN_SHORT
+    a.counters = sc.counters;
     a.out_rows = out_rows;
     a.m = m;
     a.n_tiles = n_tiles;

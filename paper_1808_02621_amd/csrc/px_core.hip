@@ -104,10 +104,7 @@ extern "C" const char* px_status_string(px_status s) {
 extern "C" const char* px_last_error(const px_ctx* ctx) { return ctx ? ctx->err : ""; }
 
 __global__ void px_k_clear_flag(uint32_t* __restrict__ flags) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        flags[0] = 0u;
-        flags[PXD_PARTITION_DONE] = 0u;
-    }
+    if (threadIdx.x == 0 && blockIdx.x == 0) flags[0] = 0u;
 }
 
 extern "C" px_status px_device_status(px_ctx* ctx, void* hip_stream) {
@@ -123,8 +120,6 @@ extern "C" px_status px_device_status(px_ctx* ctx, void* hip_stream) {
     s = px_check_hip(ctx, hipStreamSynchronize(stream), "status sync");
     if (s != PX_OK) return s;
     uint32_t f = ctx->h_flags[0];
-    if (f & PXF_INTERNAL)
-        return px_fail(ctx, PX_ERR_DEVICE, "a bounded wait between workgroups ran out; results of that call are invalid");
     if (f & PXF_BAD_ID)
         return px_fail(ctx, PX_ERR_INDEX_OUT_OF_RANGE, "a row id outside [0, vocab) reached the device");
     return PX_OK;

@@ -64,13 +64,26 @@ template <> struct In<uint16_t> {
     static __device__ __forceinline__ float widen(uint16_t v) { return __uint_as_float((uint32_t) v << 16); }
 };
 
-#ifndef PX_DENSE_PIECES
-#define PX_DENSE_PIECES 1       // 16-byte pieces per thread (a block reads PIECES * 4 KB of each buffer)
-#endif
-
+// Thread i owns piece i (16 bytes) of every buffer.
 template <typename TIN, bool OUT_BF16>
-__device__ __forceinline__ void dense_store(void* out, int64_t i, const acc_t* acc, float scale) {
+__global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ words, int n_buffers,
+                                                   int64_t pieces, void* __restrict__ out, float scale) {
     enum { E = In<TIN>::E };
+    const int64_t i = (int64_t) blockIdx.x * 256 + threadIdx.x;
+    if (i >= pieces) return;
+    const uint4* const* bufs = (const uint4* const*) words;
+    acc_t acc[E];
+#pragma unroll
+    for (int x = 0; x < E; ++x) acc[x] = (acc_t) 0;
+    for (int w0 = 0; w0 < n_buffers; w0 += DENSE_BATCH) {
+        uint4 r[DENSE_BATCH];
+#pragma unroll
+        for (int j = 0; j < DENSE_BATCH; ++j)
+            if (w0 + j < n_buffers) r[j] = load16(bufs[w0 + j] + i);
+#pragma unroll
+        for (int j = 0; j < DENSE_BATCH; ++j)
+            if (w0 + j < n_buffers) In<TIN>::add(acc, r[j]);
+    }
     float o[E];
 #pragma unroll
     for (int x = 0; x < E; ++x) o[x] = (float) (acc[x] * (acc_t) scale);
@@ -96,37 +109,6 @@ __device__ __forceinline__ void dense_store(void* out, int64_t i, const acc_t* a
     }
 }
 
-// A block owns K * 256 consecutive 16-byte pieces of every buffer; thread t owns pieces
-// t, t + 256, ... of that range.
-template <typename TIN, bool OUT_BF16, int K>
-__global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ words, int n_buffers,
-                                                   int64_t pieces, void* __restrict__ out, float scale) {
-    enum { E = In<TIN>::E };
-    const int64_t i0 = (int64_t) blockIdx.x * (256 * K) + threadIdx.x;
-    const uint4* const* bufs = (const uint4* const*) words;
-    acc_t acc[K][E];
-#pragma unroll
-    for (int k = 0; k < K; ++k)
-#pragma unroll
-        for (int x = 0; x < E; ++x) acc[k][x] = (acc_t) 0;
-    for (int w0 = 0; w0 < n_buffers; w0 += DENSE_BATCH) {
-        uint4 r[DENSE_BATCH][K];
-#pragma unroll
-        for (int j = 0; j < DENSE_BATCH; ++j)
-#pragma unroll
-            for (int k = 0; k < K; ++k)
-                if (w0 + j < n_buffers && i0 + k * 256 < pieces) r[j][k] = load16(bufs[w0 + j] + i0 + k * 256);
-#pragma unroll
-        for (int j = 0; j < DENSE_BATCH; ++j)
-#pragma unroll
-            for (int k = 0; k < K; ++k)
-                if (w0 + j < n_buffers && i0 + k * 256 < pieces) In<TIN>::add(acc[k], r[j][k]);
-    }
-#pragma unroll
-    for (int k = 0; k < K; ++k)
-        if (i0 + k * 256 < pieces) dense_store<TIN, OUT_BF16>(out, i0 + k * 256, acc[k], scale);
-}
-
 // One element per thread, for unaligned buffers and for the tail behind the last full piece.
 template <typename TIN, bool OUT_BF16>
 __global__ __launch_bounds__(256) void k_dense_scalar(const uint64_t* __restrict__ words, int n_buffers,
@@ -149,8 +131,7 @@ void launch(px_ctx* ctx, int n, int64_t count, bool vec, void* out, float scale,
     if (vec) {
         const int64_t pieces = count / E;
         if (pieces > 0)
-            k_dense_vec<TIN, OUT_BF16, PX_DENSE_PIECES><<<(unsigned) ((pieces + 256 * PX_DENSE_PIECES - 1) / (256 * PX_DENSE_PIECES)), 256, 0, stream>>>(
-                ctx->d_words, n, pieces, out, scale);
+            k_dense_vec<TIN, OUT_BF16><<<(unsigned) ((pieces + 255) / 256), 256, 0, stream>>>(ctx->d_words, n, pieces, out, scale);
         done = pieces * E;
     }
     if (done < count)

@@ -20,11 +20,7 @@ struct px_ctx {
 // and [buffer pointers] for the dense mean.
 enum { PXW_TOTAL = 3 * PX_MAX_SOURCES + 8 };
 
-enum {
-    PXF_BAD_ID = 1u,      // a row id outside the table reached the device
-    PXF_INTERNAL = 2u     // a bounded wait between workgroups ran out (never seen in practice)
-};                        // bits of d_flags[0]
-enum { PXD_PARTITION_DONE = 8 };   // d_flags[8]: blocks of the shard count kernel that have finished (returns to 0)
+enum { PXF_BAD_ID = 1u };                   // bits of d_flags[0]
 
 px_status px_fail(px_ctx* ctx, px_status s, const char* fmt, ...);
 px_status px_check_hip(px_ctx* ctx, hipError_t e, const char* what);
@@ -37,17 +33,28 @@ px_status px_upload_words(px_ctx* ctx, uint64_t* dst, const uint64_t* host_words
 static inline size_t px_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---------------------------------------------------------------- radix passes
-// One stable 8-bit counting pass ranks tiles of PX_SORT_TILE items in LDS.
+// One stable 8-bit counting pass = histogram per block, prefix over blocks, scatter.
 enum {
     PX_SORT_THREADS = 256,
     PX_SORT_ITEMS = 8,
-    PX_SORT_TILE = PX_SORT_THREADS * PX_SORT_ITEMS,
+    PX_SORT_TILE = PX_SORT_THREADS * PX_SORT_ITEMS,   // items ranked at once in LDS
+    PX_SORT_MAX_BLOCKS = 512,     // multiple of 64
     PX_RADIX = 256
 };
 
-static inline int64_t px_sort_tiles(int64_t n) {
-    int64_t t = (n + PX_SORT_TILE - 1) / PX_SORT_TILE;
-    return t < 1 ? 1 : t;
+struct px_sort_geom {
+    int n_blocks;      // blocks of a pass
+    int64_t chunk;     // items per block, a multiple of PX_SORT_TILE
+};
+
+static inline px_sort_geom px_sort_geometry(int64_t n) {
+    px_sort_geom g;
+    int64_t per = (n + PX_SORT_MAX_BLOCKS - 1) / PX_SORT_MAX_BLOCKS;
+    g.chunk = (per + PX_SORT_TILE - 1) / PX_SORT_TILE * PX_SORT_TILE;
+    if (g.chunk < PX_SORT_TILE) g.chunk = PX_SORT_TILE;
+    g.n_blocks = (int) ((n + g.chunk - 1) / g.chunk);
+    if (g.n_blocks < 1) g.n_blocks = 1;
+    return g;
 }
 
 #endif  // PX_INTERNAL_H_
