@@ -73,7 +73,16 @@ __device__ __forceinline__ void adagrad(float& w, float& a, float g, float lr, f
     w = w - lr * g / (sqrtf(a) + eps);
 }
 
-template <bool ADAGRAD, bool VEC, int G, int C>
+#ifndef PX_APPLY_BLOCKS
+#define PX_APPLY_BLOCKS 4096     // most blocks of one apply launch
+#endif
+#ifndef PX_APPLY_ROWS
+#define PX_APPLY_ROWS 1         // rows a lane group has in flight when a row is one piece per lane (2 and 4 measured no faster)
+#endif
+
+// R rows per lane group are in flight at once: their ids, then all their row pieces, are loaded
+// before anything is computed or stored.
+template <bool ADAGRAD, bool VEC, int G, int C, int R>
 __global__ __launch_bounds__(256) void k_apply(ApplyArgs p) {
     typedef typename Piece<VEC>::V V;
     enum { E = Piece<VEC>::E };
@@ -91,42 +100,61 @@ __global__ __launch_bounds__(256) void k_apply(ApplyArgs p) {
     const int gl = threadIdx.x % G;
     const int64_t group = (int64_t) blockIdx.x * (256 / G) + threadIdx.x / G;
     const int64_t n_groups = (int64_t) gridDim.x * (256 / G);
-    for (int64_t j = first + group; j < last; j += n_groups) {
-        int64_t k = p.perm ? (int64_t) p.perm[j] : j;
-        if (k < 0 || k >= n) continue;
-        const int64_t id = p.ids[k];
-        if (id < 0 || id >= p.vocab) {
-            if (gl == 0) atomicOr(p.flags, (uint32_t) PXF_BAD_ID);
-            continue;
-        }
-        const V* g = (const V*) (p.rows + (size_t) k * p.dim);
-        V* w = (V*) (p.table + (size_t) id * p.dim);
-        V* a = ADAGRAD ? (V*) (p.accum + (size_t) id * p.dim) : nullptr;
-        for (int p0 = 0; p0 < p.pieces; p0 += G * C) {
-            V gv[C], wv[C], av[C];
+    for (int64_t j0 = first + group * R; j0 < last; j0 += n_groups * R) {
+        int64_t k[R], id[R];
+        bool ok[R];
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                const int pc = p0 + c * G + gl;
-                if (pc < p.pieces) {
-                    gv[c] = load_grad(g + pc);
-                    wv[c] = load_state(w + pc);
-                    if (ADAGRAD) av[c] = load_state(a + pc);
+        for (int r = 0; r < R; ++r) {
+            ok[r] = j0 + r < last;
+            k[r] = ok[r] ? (p.perm ? (int64_t) p.perm[j0 + r] : j0 + r) : 0;
+            ok[r] = ok[r] && k[r] >= 0 && k[r] < n;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            id[r] = ok[r] ? p.ids[k[r]] : 0;
+            if (ok[r] && (id[r] < 0 || id[r] >= p.vocab)) {
+                if (gl == 0) atomicOr(p.flags, (uint32_t) PXF_BAD_ID);
+                ok[r] = false;
+            }
+        }
+        for (int p0 = 0; p0 < p.pieces; p0 += G * C) {
+            V gv[R][C], wv[R][C], av[R][C];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (!ok[r]) continue;
+                const V* g = (const V*) (p.rows + (size_t) k[r] * p.dim);
+                const V* w = (const V*) (p.table + (size_t) id[r] * p.dim);
+                const V* a = ADAGRAD ? (const V*) (p.accum + (size_t) id[r] * p.dim) : nullptr;
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    const int pc = p0 + c * G + gl;
+                    if (pc < p.pieces) {
+                        gv[r][c] = load_grad(g + pc);
+                        wv[r][c] = load_state(w + pc);
+                        if (ADAGRAD) av[r][c] = load_state(a + pc);
+                    }
                 }
             }
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                const int pc = p0 + c * G + gl;
-                if (pc < p.pieces) {
-                    float* gf = (float*) &gv[c];
-                    float* wf = (float*) &wv[c];
-                    float* af = (float*) &av[c];
+            for (int r = 0; r < R; ++r) {
+                if (!ok[r]) continue;
+                V* w = (V*) (p.table + (size_t) id[r] * p.dim);
+                V* a = ADAGRAD ? (V*) (p.accum + (size_t) id[r] * p.dim) : nullptr;
 #pragma unroll
-                    for (int x = 0; x < E; ++x) {
-                        if (ADAGRAD) adagrad(wf[x], af[x], gf[x], p.lr, p.eps);
-                        else sgd(wf[x], gf[x], p.lr);
+                for (int c = 0; c < C; ++c) {
+                    const int pc = p0 + c * G + gl;
+                    if (pc < p.pieces) {
+                        float* gf = (float*) &gv[r][c];
+                        float* wf = (float*) &wv[r][c];
+                        float* af = (float*) &av[r][c];
+#pragma unroll
+                        for (int x = 0; x < E; ++x) {
+                            if (ADAGRAD) adagrad(wf[x], af[x], gf[x], p.lr, p.eps);
+                            else sgd(wf[x], gf[x], p.lr);
+                        }
+                        store_state(w + pc, wv[r][c]);
+                        if (ADAGRAD) store_state(a + pc, av[r][c]);
                     }
-                    store_state(w + pc, wv[c]);
-                    if (ADAGRAD) store_state(a + pc, av[c]);
                 }
             }
         }
@@ -137,15 +165,15 @@ template <bool ADAGRAD, bool VEC>
 void launch(const ApplyArgs& p, hipStream_t stream) {
     auto blocks = [&](int g) {
         int64_t b = (p.cap + (256 / g) - 1) / (256 / g);
-        if (b > 4096) b = 4096;
+        if (b > PX_APPLY_BLOCKS) b = PX_APPLY_BLOCKS;
         if (b < 1) b = 1;
         return dim3((unsigned) b, 1, 1);
     };
-    if (p.pieces <= 16) k_apply<ADAGRAD, VEC, 16, 1><<<blocks(16), 256, 0, stream>>>(p);
-    else if (p.pieces <= 32) k_apply<ADAGRAD, VEC, 32, 1><<<blocks(32), 256, 0, stream>>>(p);
-    else if (p.pieces <= 64) k_apply<ADAGRAD, VEC, 64, 1><<<blocks(64), 256, 0, stream>>>(p);
-    else if (p.pieces <= 128) k_apply<ADAGRAD, VEC, 64, 2><<<blocks(64), 256, 0, stream>>>(p);
-    else k_apply<ADAGRAD, VEC, 64, 4><<<blocks(64), 256, 0, stream>>>(p);
+    if (p.pieces <= 16) k_apply<ADAGRAD, VEC, 16, 1, PX_APPLY_ROWS><<<blocks(16), 256, 0, stream>>>(p);
+    else if (p.pieces <= 32) k_apply<ADAGRAD, VEC, 32, 1, PX_APPLY_ROWS><<<blocks(32), 256, 0, stream>>>(p);
+    else if (p.pieces <= 64) k_apply<ADAGRAD, VEC, 64, 1, PX_APPLY_ROWS><<<blocks(64), 256, 0, stream>>>(p);
+    else if (p.pieces <= 128) k_apply<ADAGRAD, VEC, 64, 2, 1><<<blocks(64), 256, 0, stream>>>(p);
+    else k_apply<ADAGRAD, VEC, 64, 4, 1><<<blocks(64), 256, 0, stream>>>(p);
 }
 
 px_status apply_common(px_ctx* ctx, bool adagrad, float* table, float* accum, int64_t vocab, int64_t dim,
