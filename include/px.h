@@ -14,6 +14,8 @@
  *   px_sparse_apply_sgd      update the touched rows in place, gradient descent
  *   px_sparse_apply_adagrad  update the touched rows in place, Adagrad
  *   px_dense_average         reduce N workers' dense gradient buffers (sum or mean)
+ * and, fused, the first and third of these without the aggregated rows ever being stored:
+ *   px_sparse_coalesce_apply_sgd / px_sparse_coalesce_apply_adagrad
  *
  * Conventions for every call
  *   - "dev" pointers are device (HBM) addresses on the context's GPU; "host"
@@ -166,6 +168,30 @@ px_status px_sparse_apply_adagrad(px_ctx* ctx, float* table, float* accum, int64
                                   int64_t dim, const int64_t* ids, const float* rows,
                                   const int64_t* num_ids, int64_t cap, const int32_t* perm,
                                   const int64_t* range, float lr, float eps, void* hip_stream);
+
+/*
+ * Aggregate and update in one go (Sec. 4.3: the global aggregation is placed on the server that
+ * holds the variable, so the aggregated gradient never travels; here it is never written to
+ * memory).  Same result as px_sparse_coalesce followed by px_sparse_apply_sgd /
+ * px_sparse_apply_adagrad over all rows (perm = NULL, range = NULL), bit for bit: the sum of a
+ * run is rounded to float, scaled, and fed to the same update arithmetic.
+ * Arguments as in those two calls; there is no out_rows.  out_ids, out_num_unique and
+ * out_run_len are still produced (px_partition_rows can run on them afterwards).
+ * An id outside [0, vocab) raises the context's flag and leaves table and accum untouched.
+ */
+px_status px_sparse_coalesce_apply_sgd(px_ctx* ctx, int n_workers, const int64_t* const* idx,
+                                       const void* const* val, const int64_t* counts, int64_t dim,
+                                       px_dtype val_dtype, int64_t vocab, float scale, float* table,
+                                       float lr, int64_t* out_ids, int64_t* out_num_unique,
+                                       int32_t* out_run_len, void* scratch, size_t scratch_bytes,
+                                       void* hip_stream);
+
+px_status px_sparse_coalesce_apply_adagrad(px_ctx* ctx, int n_workers, const int64_t* const* idx,
+                                           const void* const* val, const int64_t* counts, int64_t dim,
+                                           px_dtype val_dtype, int64_t vocab, float scale, float* table,
+                                           float* accum, float lr, float eps, int64_t* out_ids,
+                                           int64_t* out_num_unique, int32_t* out_run_len, void* scratch,
+                                           size_t scratch_bytes, void* hip_stream);
 
 /*
  * Dense gradient aggregation (Sec. 2.1: AllReduce computes the sum over the N

@@ -7,6 +7,7 @@
 // (and accumulator row), the update, 128-bit stores.  Rows are taken in the order
 // perm gives, restricted to [range[0], range[1]) when a shard range is passed.
 #include "px_internal.h"
+#include "px_update.h"
 
 namespace {
 
@@ -67,11 +68,6 @@ __device__ __forceinline__ void store_state(float4* p, float4 v) {
 }
 __device__ __forceinline__ void store_state(float* p, float v) { *p = v; }
 
-__device__ __forceinline__ void sgd(float& w, float g, float lr) { w = w - lr * g; }
-__device__ __forceinline__ void adagrad(float& w, float& a, float g, float lr, float eps) {
-    a = a + g * g;
-    w = w - lr * g / (sqrtf(a) + eps);
-}
 
 #ifndef PX_APPLY_BLOCKS
 #define PX_APPLY_BLOCKS 4096     // most blocks of one apply launch
@@ -149,8 +145,8 @@ __global__ __launch_bounds__(256) void k_apply(ApplyArgs p) {
                         float* af = (float*) &av[r][c];
 #pragma unroll
                         for (int x = 0; x < E; ++x) {
-                            if (ADAGRAD) adagrad(wf[x], af[x], gf[x], p.lr, p.eps);
-                            else sgd(wf[x], gf[x], p.lr);
+                            if (ADAGRAD) pxu::adagrad(wf[x], af[x], gf[x], p.lr, p.eps);
+                            else pxu::sgd(wf[x], gf[x], p.lr);
                         }
                         store_state(w + pc, wv[r][c]);
                         if (ADAGRAD) store_state(a + pc, av[r][c]);

@@ -17,7 +17,10 @@
 //   5. fixup   each split run adds up its partial rows, rounds once, writes its row
 // Nothing waits on another workgroup and global atomics only append to the list of split
 // runs, so the sums are deterministic.
+#include <type_traits>
+
 #include "px_radix.h"
+#include "px_update.h"
 
 namespace {
 
@@ -364,6 +367,8 @@ template <> struct RowLoad<uint16_t, false> {
     }
 };
 
+enum { MODE_ROWS = 0, MODE_SGD = 1, MODE_ADAGRAD = 2 };   // what becomes of a finished run
+
 struct SegsumArgs {
     const uint64_t* sorted;       // packed words in id order
     const uint64_t* words;        // context table: [idx pointers | value pointers | prefix]
@@ -374,7 +379,10 @@ struct SegsumArgs {
     uint4* span_long;
     uint4* span_short;
     uint32_t* counters;
-    float* out_rows;
+    float* out_rows;              // MODE_ROWS: the aggregated rows
+    float* table;                 // fused modes: the variable, updated in place
+    float* accum;                 // MODE_ADAGRAD: its accumulator
+    const uint32_t* flags;
     int64_t m;
     int64_t n_tiles;
     int64_t dim;                  // elements per row
@@ -385,6 +393,8 @@ struct SegsumArgs {
     int tile_rows;
     int pieces;                   // row pieces (E elements each) per row
     float scale;
+    float lr;
+    float eps;
 };
 
 // G lanes walk one tile; lane l owns pieces slab*G*C + c*G + l, c < C, E elements each.
@@ -395,14 +405,23 @@ struct SegsumArgs {
 // their windows holds a head and the run goes on into the next block) their partial rows are
 // added in LDS, in tile order, and stored once, as the partial row of the block's first tile: a
 // long run then leaves one partial row per block instead of one per tile.
-template <typename T, bool VEC, int G, int C, int B>
+//
+// MODE_ROWS writes a finished run's sum as a float row.  The fused modes apply the optimizer to
+// the variable's row instead (Parallax Sec. 4.3 puts the aggregation next to the variable so the
+// aggregate never travels): the words of the next B rows are known before their value rows are
+// requested, so the table (and accumulator) rows of the runs that finish among them are
+// requested in the same breath and have arrived when the sum is complete.
+template <typename T, bool VEC, int G, int C, int B, int MODE>
 __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
     typedef RowLoad<T, VEC> L;
-    enum { E = L::E, TPB = 256 / G, MERGE = (C * E <= 16) ? 1 : 0 };
+    enum { E = L::E, TPB = 256 / G, MERGE = (C * E <= 16) ? 1 : 0, FUSED = MODE != MODE_ROWS ? 1 : 0,
+           SV = VEC ? E / 4 : 1 };                                // state vectors (float4 or float) per piece
+    typedef typename std::conditional<VEC, float4, float>::type StateV;
     __shared__ uint64_t s_base[PX_MAX_SOURCES];
     __shared__ double s_part[MERGE ? TPB * G * C * E : 1];
     for (int i = threadIdx.x; i < a.n_workers; i += 256) s_base[i] = a.words[a.n_workers + i];
     __syncthreads();
+    if (FUSED && (a.flags[0] & PXF_BAD_ID)) return;               // uniform: a bad id was seen, touch nothing
 
     const int gl = threadIdx.x % G;
     const int gj = threadIdx.x / G;                               // tile inside the block
@@ -443,6 +462,13 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
 #pragma unroll
         for (int x = 0; x < E; ++x) acc[c][x] = (seg_acc_t) 0;
 
+    auto clear = [&]() {
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int x = 0; x < E; ++x) acc[c][x] = (seg_acc_t) 0;
+    };
+
     auto store_partial = [&](double* dst) {
 #pragma unroll
         for (int c = 0; c < C; ++c) {
@@ -458,48 +484,59 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
         }
     };
 
-    auto flush = [&](bool ended) {
-        if (started && ended) {
-            float* dst = a.out_rows + (size_t) u * a.dim;
-#pragma unroll
-            for (int c = 0; c < C; ++c)
-                if (live[c]) {
-                    if (VEC) {
-#pragma unroll
-                        for (int x = 0; x < E; x += 4) {
-                            float4 o = make_float4((float) ((double) acc[c][x] * a.scale), (float) ((double) acc[c][x + 1] * a.scale),
-                                                   (float) ((double) acc[c][x + 2] * a.scale), (float) ((double) acc[c][x + 3] * a.scale));
-                            seg_store16(dst + (size_t) piece[c] * E + x, o);
-                        }
-                    } else {
-                        dst[piece[c]] = (float) ((double) acc[c][0] * a.scale);
-                    }
-                }
-        } else {
-            store_partial((started ? a.plast : a.pfirst) + (size_t) tile * a.pstride);
-            if (started && gl == 0 && blockIdx.y == 0) {
-                // this tile holds the head of a run that goes on: record where the run ends
-                const uint32_t last_row = a.run_start[u + 1] - 1u;
-                uint32_t last_tile = last_row / (uint32_t) a.tile_rows;
-                if (a.tile_info[last_tile].x > last_row) --last_tile;
-                const bool is_long = last_tile - (uint32_t) tile > (uint32_t) SPAN_LONG_TILES;
-                const uint32_t slot = atomicAdd(a.counters + (is_long ? 0 : 1), 1u);
-                (is_long ? a.span_long : a.span_short)[slot] = make_uint4(u, (uint32_t) tile, last_tile, 0u);
-            }
+    // a run that started in this tile goes on into the next one
+    auto leave_open = [&]() {
+        store_partial(a.plast + (size_t) tile * a.pstride);
+        if (gl == 0 && blockIdx.y == 0) {
+            // record where the run ends
+            const uint32_t last_row = a.run_start[u + 1] - 1u;
+            uint32_t last_tile = last_row / (uint32_t) a.tile_rows;
+            if (a.tile_info[last_tile].x > last_row) --last_tile;
+            const bool is_long = last_tile - (uint32_t) tile > (uint32_t) SPAN_LONG_TILES;
+            const uint32_t slot = atomicAdd(a.counters + (is_long ? 0 : 1), 1u);
+            (is_long ? a.span_long : a.span_short)[slot] = make_uint4(u, (uint32_t) tile, last_tile, 0u);
         }
+    };
+
+    // a run that lies wholly inside this tile: MODE_ROWS
+    auto write_row = [&]() {
+        float* dst = a.out_rows + (size_t) u * a.dim;
 #pragma unroll
         for (int c = 0; c < C; ++c)
+            if (live[c]) {
+                if (VEC) {
 #pragma unroll
-            for (int x = 0; x < E; ++x) acc[c][x] = (seg_acc_t) 0;
+                    for (int x = 0; x < E; x += 4) {
+                        float4 o = make_float4((float) ((double) acc[c][x] * a.scale), (float) ((double) acc[c][x + 1] * a.scale),
+                                               (float) ((double) acc[c][x + 2] * a.scale), (float) ((double) acc[c][x + 3] * a.scale));
+                        seg_store16(dst + (size_t) piece[c] * E + x, o);
+                    }
+                } else {
+                    dst[piece[c]] = (float) ((double) acc[c][0] * a.scale);
+                }
+            }
     };
 
     if (active) {
-        uint32_t cur = key_of(a.sorted[s]);
         for (int64_t r = s; r < e; r += B) {
-            uint64_t w[B];
+            uint64_t w[B + 1];
             typename L::Raw raw[B][C];
+            StateV wst[FUSED ? B : 1][C][SV];
+            StateV ast[MODE == MODE_ADAGRAD ? B : 1][C][SV];
 #pragma unroll
-            for (int j = 0; j < B; ++j) w[j] = (r + j < e) ? a.sorted[r + j] : 0ull;
+            for (int j = 0; j <= B; ++j) w[j] = (r + j < e) ? a.sorted[r + j] : 0ull;
+            // which rows of the batch finish a run, and is that run wholly inside the tile?
+            bool ends[B], whole[B];
+            {
+                bool st = started;
+#pragma unroll
+                for (int j = 0; j < B; ++j) {
+                    const bool last_of_tile = r + j + 1 >= e;
+                    ends[j] = (r + j < e) && (last_of_tile || key_of(w[j + 1]) != key_of(w[j]));
+                    whole[j] = ends[j] && st && (!last_of_tile || next_is_head);
+                    if (ends[j]) st = true;
+                }
+            }
 #pragma unroll
             for (int j = 0; j < B; ++j) {
                 if (r + j < e) {
@@ -509,25 +546,71 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
 #pragma unroll
                     for (int c = 0; c < C; ++c)
                         if (live[c]) raw[j][c] = L::load(row + (size_t) piece[c] * (E * sizeof(T)));
+                    if (FUSED && whole[j]) {
+                        const size_t off = (size_t) key_of(w[j]) * a.dim;
+#pragma unroll
+                        for (int c = 0; c < C; ++c)
+                            if (live[c]) {
+#pragma unroll
+                                for (int v = 0; v < SV; ++v) {
+                                    wst[j][c][v] = ((const StateV*) (a.table + off + (size_t) piece[c] * E))[v];
+                                    if (MODE == MODE_ADAGRAD)
+                                        ast[j][c][v] = ((const StateV*) (a.accum + off + (size_t) piece[c] * E))[v];
+                                }
+                            }
+                    }
                 }
             }
 #pragma unroll
             for (int j = 0; j < B; ++j) {
                 if (r + j < e) {
-                    const uint32_t k = key_of(w[j]);
-                    if (k != cur) {
-                        flush(true);
-                        ++u;
-                        cur = k;
-                        started = true;
-                    }
 #pragma unroll
                     for (int c = 0; c < C; ++c)
                         if (live[c]) L::add(acc[c], raw[j][c]);
+                    if (ends[j]) {
+                        const bool last_of_tile = r + j + 1 >= e;
+                        if (whole[j]) {
+                            if (!FUSED) {
+                                write_row();
+                            } else {
+                                const size_t off = (size_t) key_of(w[j]) * a.dim;
+#pragma unroll
+                                for (int c = 0; c < C; ++c)
+                                    if (live[c]) {
+                                        float* wf = (float*) &wst[j][c][0];
+                                        float* af = (float*) &ast[MODE == MODE_ADAGRAD ? j : 0][c][0];
+#pragma unroll
+                                        for (int x = 0; x < E; ++x) {
+                                            const float g = (float) ((double) acc[c][x] * a.scale);
+                                            if (MODE == MODE_ADAGRAD) pxu::adagrad(wf[x], af[x], g, a.lr, a.eps);
+                                            else pxu::sgd(wf[x], g, a.lr);
+                                        }
+#pragma unroll
+                                        for (int v = 0; v < SV; ++v) {
+                                            ((StateV*) (a.table + off + (size_t) piece[c] * E))[v] = wst[j][c][v];
+                                            if (MODE == MODE_ADAGRAD)
+                                                ((StateV*) (a.accum + off + (size_t) piece[c] * E))[v] = ast[j][c][v];
+                                        }
+                                    }
+                            }
+                            clear();
+                        } else if (last_of_tile && merged) {
+                            // keep the sum: the block adds its tiles up below
+                        } else if (started) {
+                            leave_open();                       // only the tile's last run can stay open
+                            clear();
+                        } else {
+                            store_partial(a.pfirst + (size_t) tile * a.pstride);     // entered from the tile before
+                            clear();
+                        }
+                        if (!last_of_tile) {
+                            ++u;
+                            started = true;
+                        }
+                    }
                 }
             }
         }
-        if (!merged) flush(next_is_head);
     }
 
     if (MERGE && merged) {                                    // uniform over the block
@@ -562,6 +645,12 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
 enum { FIX_SPLITS = 16 };
 
 struct FixupArgs {
+    int mode;                     // MODE_ROWS, MODE_SGD or MODE_ADAGRAD
+    float* table;
+    float* accum;
+    const int64_t* out_ids;
+    const uint32_t* flags;
+    float lr, eps;
     const uint4* span_long;
     const uint4* span_short;
     const uint32_t* counters;
@@ -610,8 +699,28 @@ struct PartList {
     }
 };
 
+// What becomes of a split run's column once its sum is known.
+__device__ __forceinline__ void fixup_finish(const FixupArgs& a, uint32_t u, int64_t col, double sum) {
+    const float g = (float) (sum * a.scale);
+    if (a.mode == MODE_ROWS) {
+        a.out_rows[(size_t) u * a.dim + col] = g;
+        return;
+    }
+    const size_t at = (size_t) a.out_ids[u] * a.dim + col;
+    float w = a.table[at];
+    if (a.mode == MODE_ADAGRAD) {
+        float acc = a.accum[at];
+        pxu::adagrad(w, acc, g, a.lr, a.eps);
+        a.accum[at] = acc;
+    } else {
+        pxu::sgd(w, g, a.lr);
+    }
+    a.table[at] = w;
+}
+
 __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
     __shared__ double s_red[FIX_SPLITS][64];
+    if (a.mode != MODE_ROWS && (a.flags[0] & PXF_BAD_ID)) return;   // uniform: a bad id was seen, touch nothing
     const int lane = threadIdx.x & 63, split = threadIdx.x >> 6;
     const int64_t pe = (int64_t) blockIdx.y * 64 + lane;          // slot in the partial row
     // which column does slot pe hold?
@@ -646,7 +755,7 @@ __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
             double tsum = 0.0;
 #pragma unroll
             for (int w = 0; w < FIX_SPLITS; ++w) tsum += s_red[w][lane];
-            a.out_rows[(size_t) rec.x * a.dim + col] = (float) (tsum * a.scale);
+            fixup_finish(a, rec.x, col, tsum);
         }
         __syncthreads();
     }
@@ -664,7 +773,7 @@ __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
                 for (int j = 0; j < 4; ++j) acc += v[j];
             }
             for (; q < pl.parts; ++q) acc += pl.row(q, a.pfirst, a.plast, a.pstride)[pe];
-            a.out_rows[(size_t) rec.x * a.dim + col] = (float) (acc * a.scale);
+            fixup_finish(a, rec.x, col, acc);
         }
     }
     if (a.out_run_len != nullptr && blockIdx.y == 0) {
@@ -684,14 +793,34 @@ int bits_for(uint64_t max_value) {   // bits needed to write max_value
     return b;
 }
 
-template <typename T, bool VEC>
+// Rows in flight per lane group.  The fused modes also hold the table (and accumulator) pieces of
+// every row of a batch that may finish a run, so their batches shrink as rows get wider.
+constexpr int batch_rows(int mode, int c, int state_vectors) {
+    if (mode == MODE_ROWS) return c <= 2 ? PX_SEG_ROWS : PX_SEG_ROWS_WIDE;
+    const int per_row = c * state_vectors * (mode == MODE_ADAGRAD ? 2 : 1);
+    return per_row >= 8 ? 1 : 8 / per_row;
+}
+
+template <typename T, bool VEC, int MODE>
 void launch_segsum(const SegsumArgs& a, const RowShape& sh, hipStream_t stream) {
+    constexpr int SV = VEC ? RowLoad<T, VEC>::E / 4 : 1;
     const dim3 grid((unsigned) ((a.n_tiles + (256 / sh.G) - 1) / (256 / sh.G)), (unsigned) sh.slabs, 1);
-    if (sh.G == 16) k_segsum<T, VEC, 16, 1, PX_SEG_ROWS><<<grid, 256, 0, stream>>>(a);
-    else if (sh.G == 32) k_segsum<T, VEC, 32, 1, PX_SEG_ROWS><<<grid, 256, 0, stream>>>(a);
-    else if (sh.C == 1) k_segsum<T, VEC, 64, 1, PX_SEG_ROWS><<<grid, 256, 0, stream>>>(a);
-    else if (sh.C == 2) k_segsum<T, VEC, 64, 2, PX_SEG_ROWS><<<grid, 256, 0, stream>>>(a);
-    else k_segsum<T, VEC, 64, 4, PX_SEG_ROWS_WIDE><<<grid, 256, 0, stream>>>(a);
+    if (sh.G == 16) k_segsum<T, VEC, 16, 1, batch_rows(MODE, 1, SV), MODE><<<grid, 256, 0, stream>>>(a);
+    else if (sh.G == 32) k_segsum<T, VEC, 32, 1, batch_rows(MODE, 1, SV), MODE><<<grid, 256, 0, stream>>>(a);
+    else if (sh.C == 1) k_segsum<T, VEC, 64, 1, batch_rows(MODE, 1, SV), MODE><<<grid, 256, 0, stream>>>(a);
+    else if (sh.C == 2) k_segsum<T, VEC, 64, 2, batch_rows(MODE, 2, SV), MODE><<<grid, 256, 0, stream>>>(a);
+    else k_segsum<T, VEC, 64, 4, batch_rows(MODE, 4, SV), MODE><<<grid, 256, 0, stream>>>(a);
+}
+
+template <int MODE>
+void launch_segsum_mode(const SegsumArgs& a, const RowShape& sh, bool vec, px_dtype val_dtype, hipStream_t stream) {
+    if (vec) {
+        if (val_dtype == PX_F32) launch_segsum<float, true, MODE>(a, sh, stream);
+        else launch_segsum<uint16_t, true, MODE>(a, sh, stream);
+    } else {
+        if (val_dtype == PX_F32) launch_segsum<float, false, MODE>(a, sh, stream);
+        else launch_segsum<uint16_t, false, MODE>(a, sh, stream);
+    }
 }
 
 }  // namespace
@@ -702,12 +831,12 @@ extern "C" size_t px_coalesce_scratch_bytes(int64_t total_rows, int64_t dim) {
     return carve(nullptr, total_rows, dim).bytes;
 }
 
-extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_t* const* idx,
-                                        const void* const* val, const int64_t* counts, int64_t dim,
-                                        px_dtype val_dtype, int64_t vocab, float scale,
-                                        int64_t* out_ids, float* out_rows, int64_t* out_num_unique,
-                                        int32_t* out_run_len, void* scratch, size_t scratch_bytes,
-                                        void* hip_stream) {
+static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int64_t* const* idx,
+                                 const void* const* val, const int64_t* counts, int64_t dim,
+                                 px_dtype val_dtype, int64_t vocab, float scale, int64_t* out_ids,
+                                 float* out_rows, float* table, float* accum, float lr, float eps,
+                                 int64_t* out_num_unique, int32_t* out_run_len, void* scratch,
+                                 size_t scratch_bytes, void* hip_stream) {
     if (!ctx) return PX_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t) hip_stream;
     if (n_workers < 1 || n_workers > PX_MAX_SOURCES)
@@ -737,9 +866,18 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
         k_write_zero_count<<<1, 64, 0, stream>>>(out_num_unique);
         return px_check_hip(ctx, hipGetLastError(), "launch");
     }
-    if (!out_ids || !out_rows || !scratch) return px_fail(ctx, PX_ERR_INVALID_ARG, "null output or scratch");
-    if (((uintptr_t) scratch) % 256 || ((uintptr_t) out_rows) % 16)
-        return px_fail(ctx, PX_ERR_INVALID_ARG, "scratch needs 256-byte and out_rows 16-byte alignment");
+    if (!out_ids || !scratch) return px_fail(ctx, PX_ERR_INVALID_ARG, "null output or scratch");
+    if (((uintptr_t) scratch) % 256) return px_fail(ctx, PX_ERR_INVALID_ARG, "scratch needs 256-byte alignment");
+    if (mode == MODE_ROWS) {
+        if (!out_rows || ((uintptr_t) out_rows) % 16)
+            return px_fail(ctx, PX_ERR_INVALID_ARG, "out_rows null or not 16-byte aligned");
+    } else {
+        if (!table || (mode == MODE_ADAGRAD && !accum)) return px_fail(ctx, PX_ERR_INVALID_ARG, "null table or accumulator");
+        if (((uintptr_t) table) % 4 || (accum && ((uintptr_t) accum) % 4))
+            return px_fail(ctx, PX_ERR_INVALID_ARG, "float pointers misaligned");
+        // the 128-bit path also reads and writes the variable in 16-byte pieces
+        if (dim % 4 || ((uintptr_t) table) % 16 || (accum && ((uintptr_t) accum) % 16)) vec = false;
+    }
     const int local_bits = bits_for((uint64_t) (max_count - 1));
     if (bits_for((uint64_t) (n_workers - 1)) + local_bits > 32)
         return px_fail(ctx, PX_ERR_INVALID_ARG, "bits(n_workers-1) + bits(max count-1) exceeds 32");
@@ -808,14 +946,22 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
     a.tile_rows = tile_rows;
     a.pieces = sh.pieces;
     a.scale = scale;
-    if (vec) {
-        if (val_dtype == PX_F32) launch_segsum<float, true>(a, sh, stream);
-        else launch_segsum<uint16_t, true>(a, sh, stream);
-    } else {
-        if (val_dtype == PX_F32) launch_segsum<float, false>(a, sh, stream);
-        else launch_segsum<uint16_t, false>(a, sh, stream);
-    }
+    a.table = table;
+    a.accum = accum;
+    a.flags = ctx->d_flags;
+    a.lr = lr;
+    a.eps = eps;
+    if (mode == MODE_ROWS) launch_segsum_mode<MODE_ROWS>(a, sh, vec, val_dtype, stream);
+    else if (mode == MODE_SGD) launch_segsum_mode<MODE_SGD>(a, sh, vec, val_dtype, stream);
+    else launch_segsum_mode<MODE_ADAGRAD>(a, sh, vec, val_dtype, stream);
     FixupArgs f;
+    f.mode = mode;
+    f.table = table;
+    f.accum = accum;
+    f.out_ids = out_ids;
+    f.flags = ctx->d_flags;
+    f.lr = lr;
+    f.eps = eps;
     f.span_long = sc.span_long;
     f.span_short = sc.span_short;
     f.counters = sc.counters;
@@ -836,4 +982,38 @@ extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_
     const unsigned fx = (unsigned) (n_tiles < 64 ? n_tiles : 64);
     k_fixup<<<dim3(fx, (unsigned) ((sh.pstride + 63) / 64), 1), 64 * FIX_SPLITS, 0, stream>>>(f);
     return px_check_hip(ctx, hipGetLastError(), "coalesce launch");
+}
+
+extern "C" px_status px_sparse_coalesce(px_ctx* ctx, int n_workers, const int64_t* const* idx,
+                                        const void* const* val, const int64_t* counts, int64_t dim,
+                                        px_dtype val_dtype, int64_t vocab, float scale,
+                                        int64_t* out_ids, float* out_rows, int64_t* out_num_unique,
+                                        int32_t* out_run_len, void* scratch, size_t scratch_bytes,
+                                        void* hip_stream) {
+    return coalesce_common(ctx, MODE_ROWS, n_workers, idx, val, counts, dim, val_dtype, vocab, scale, out_ids,
+                           out_rows, nullptr, nullptr, 0.f, 0.f, out_num_unique, out_run_len, scratch,
+                           scratch_bytes, hip_stream);
+}
+
+extern "C" px_status px_sparse_coalesce_apply_sgd(px_ctx* ctx, int n_workers, const int64_t* const* idx,
+                                                  const void* const* val, const int64_t* counts, int64_t dim,
+                                                  px_dtype val_dtype, int64_t vocab, float scale, float* table,
+                                                  float lr, int64_t* out_ids, int64_t* out_num_unique,
+                                                  int32_t* out_run_len, void* scratch, size_t scratch_bytes,
+                                                  void* hip_stream) {
+    return coalesce_common(ctx, MODE_SGD, n_workers, idx, val, counts, dim, val_dtype, vocab, scale, out_ids,
+                           nullptr, table, nullptr, lr, 0.f, out_num_unique, out_run_len, scratch, scratch_bytes,
+                           hip_stream);
+}
+
+extern "C" px_status px_sparse_coalesce_apply_adagrad(px_ctx* ctx, int n_workers, const int64_t* const* idx,
+                                                      const void* const* val, const int64_t* counts,
+                                                      int64_t dim, px_dtype val_dtype, int64_t vocab,
+                                                      float scale, float* table, float* accum, float lr,
+                                                      float eps, int64_t* out_ids, int64_t* out_num_unique,
+                                                      int32_t* out_run_len, void* scratch, size_t scratch_bytes,
+                                                      void* hip_stream) {
+    return coalesce_common(ctx, MODE_ADAGRAD, n_workers, idx, val, counts, dim, val_dtype, vocab, scale, out_ids,
+                           nullptr, table, accum, lr, eps, out_num_unique, out_run_len, scratch, scratch_bytes,
+                           hip_stream);
 }

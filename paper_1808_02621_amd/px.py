@@ -34,6 +34,7 @@ EXPORTS = [
     "px_create", "px_destroy", "px_status_string", "px_last_error", "px_device_status",
     "px_coalesce_scratch_bytes", "px_partition_scratch_bytes", "px_sparse_coalesce",
     "px_partition_rows", "px_sparse_apply_sgd", "px_sparse_apply_adagrad", "px_dense_average",
+    "px_sparse_coalesce_apply_sgd", "px_sparse_coalesce_apply_adagrad",
 ]
 
 if not os.path.exists(LIBRARY):
@@ -65,6 +66,12 @@ lib.px_partition_scratch_bytes.argtypes = [_i64]
 lib.px_sparse_coalesce.restype = _int
 lib.px_sparse_coalesce.argtypes = [_vp, _int, _pp, _pp, _i64p, _i64, _int, _i64, _f32, _vp, _vp, _vp,
                                    _vp, _vp, _sz, _vp]
+lib.px_sparse_coalesce_apply_sgd.restype = _int
+lib.px_sparse_coalesce_apply_sgd.argtypes = [_vp, _int, _pp, _pp, _i64p, _i64, _int, _i64, _f32, _vp, _f32, _vp,
+                                             _vp, _vp, _vp, _sz, _vp]
+lib.px_sparse_coalesce_apply_adagrad.restype = _int
+lib.px_sparse_coalesce_apply_adagrad.argtypes = [_vp, _int, _pp, _pp, _i64p, _i64, _int, _i64, _f32, _vp, _vp,
+                                                 _f32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.px_partition_rows.restype = _int
 lib.px_partition_rows.argtypes = [_vp, _vp, _vp, _i64, _int, _int, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.px_sparse_apply_sgd.restype = _int
@@ -159,6 +166,44 @@ class Context:
         self._check(lib.px_sparse_coalesce(
             self._h, n, _ptr_array(idx), _ptr_array(val), counts, dim, code, vocab, scale,
             _ptr(out_ids), _ptr(out_rows), _ptr(out_num_unique), _ptr(out_run_len), _ptr(scratch),
+            scratch.numel() * scratch.element_size(), _stream(stream)))
+
+    def _coalesce_inputs(self, idx, val, dim):
+        n = len(idx)
+        assert len(val) == n and n >= 1
+        code = _dtype_code(val[0])
+        counts = (ctypes.c_int64 * n)(*[int(i.numel()) for i in idx])
+        for i, v in zip(idx, val):
+            assert i.dtype == torch.int64 and i.is_contiguous() and v.is_contiguous()
+            assert _dtype_code(v) == code and v.numel() == i.numel() * dim
+        return n, code, counts
+
+    def px_sparse_coalesce_apply_sgd(self, idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor],
+                                     vocab: int, scale: float, table: torch.Tensor, lr: float,
+                                     out_ids: torch.Tensor, out_num_unique: torch.Tensor,
+                                     out_run_len: Optional[torch.Tensor], scratch: torch.Tensor,
+                                     stream=None) -> None:
+        assert table.dtype == torch.float32 and table.is_contiguous() and table.shape[0] == vocab
+        dim = table.shape[1]
+        n, code, counts = self._coalesce_inputs(idx, val, dim)
+        self._check(lib.px_sparse_coalesce_apply_sgd(
+            self._h, n, _ptr_array(idx), _ptr_array(val), counts, dim, code, vocab, scale, _ptr(table), lr,
+            _ptr(out_ids), _ptr(out_num_unique), _ptr(out_run_len), _ptr(scratch),
+            scratch.numel() * scratch.element_size(), _stream(stream)))
+
+    def px_sparse_coalesce_apply_adagrad(self, idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor],
+                                         vocab: int, scale: float, table: torch.Tensor,
+                                         accum: torch.Tensor, lr: float, eps: float,
+                                         out_ids: torch.Tensor, out_num_unique: torch.Tensor,
+                                         out_run_len: Optional[torch.Tensor], scratch: torch.Tensor,
+                                         stream=None) -> None:
+        assert table.dtype == torch.float32 and table.is_contiguous() and table.shape[0] == vocab
+        assert accum.dtype == torch.float32 and accum.is_contiguous() and accum.shape == table.shape
+        dim = table.shape[1]
+        n, code, counts = self._coalesce_inputs(idx, val, dim)
+        self._check(lib.px_sparse_coalesce_apply_adagrad(
+            self._h, n, _ptr_array(idx), _ptr_array(val), counts, dim, code, vocab, scale, _ptr(table),
+            _ptr(accum), lr, eps, _ptr(out_ids), _ptr(out_num_unique), _ptr(out_run_len), _ptr(scratch),
             scratch.numel() * scratch.element_size(), _stream(stream)))
 
     def px_partition_rows(self, ids: torch.Tensor, num_ids: torch.Tensor, cap: int, num_shards: int,

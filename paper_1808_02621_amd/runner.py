@@ -93,3 +93,17 @@ def sparse_step(ctx: px.Context, b: SparseBuffers, table: torch.Tensor, accum: O
     coalesce(ctx, b, scale, stream)
     partition(ctx, b, stream)
     apply(ctx, b, table, accum, optimizer, lr, stream=stream)
+
+
+def fused_step(ctx: px.Context, b: SparseBuffers, table: torch.Tensor, accum: Optional[torch.Tensor],
+               optimizer: str, lr: float, scale: float = 1.0, eps: float = 0.0, stream=None) -> None:
+    """Aggregate and update in one call (the aggregated rows are never stored), then partition the ids."""
+    if optimizer == "sgd":
+        ctx.px_sparse_coalesce_apply_sgd(b.idx, b.val, b.vocab, scale, table, lr, b.out_ids, b.out_num,
+                                         b.out_run_len, b.scratch, stream)
+    elif optimizer == "adagrad":
+        ctx.px_sparse_coalesce_apply_adagrad(b.idx, b.val, b.vocab, scale, table, accum, lr, eps, b.out_ids,
+                                             b.out_num, b.out_run_len, b.scratch, stream)
+    else:
+        raise ValueError(optimizer)
+    partition(ctx, b, stream)

@@ -81,6 +81,22 @@ def run_chain(gpu, idx, val, dim, vocab, n_shards, hash_name, optimizer, lr, tab
     assert np.array_equal(g_table[untouched], table[untouched])
     if accum is not None:
         assert np.array_equal(g_accum[untouched], accum[untouched])
+
+    # the fused aggregate-and-apply entry points: same bits as the three separate calls
+    f_table = torch.from_numpy(table).cuda()
+    f_accum = None if accum is None else torch.from_numpy(accum).cuda()
+    fb = runner.sparse_buffers(d_idx, d_val, dim, vocab, n_shards, hash_code)
+    fb.out_rows.fill_(float("nan"))                      # never written by the fused path
+    runner.fused_step(ctx, fb, f_table, f_accum, optimizer, lr, scale)
+    assert ctx.px_device_status() == px.PX_OK
+    assert int(fb.out_num.item()) == u
+    assert torch.equal(fb.out_ids[:u], b.out_ids[:u]) and torch.equal(fb.out_run_len[:u], b.out_run_len[:u])
+    assert torch.equal(fb.perm[:u], b.perm[:u]) and torch.equal(fb.offsets, b.offsets)
+    assert torch.equal(f_table, d_table), "fused and separate paths differ in %d table elements" % int(
+        (f_table != d_table).sum())
+    if accum is not None:
+        assert torch.equal(f_accum, d_accum)
+    assert bool(torch.isnan(fb.out_rows).all())
     return b, u
 
 
@@ -294,6 +310,11 @@ def test_out_of_range_id_raises_the_flag_and_protects_the_table(gpu):
         assert torch.equal(table, before)
         assert ctx.px_device_status() == px.PX_ERR_INDEX_OUT_OF_RANGE
         assert ctx.px_device_status() == px.PX_OK          # reported once, then cleared
+        accum = torch.ones_like(table)
+        runner.fused_step(ctx, b, table, accum, "adagrad", 0.5)
+        assert int(b.out_num.item()) == 0
+        assert torch.equal(table, before) and bool((accum == 1).all())
+        assert ctx.px_device_status() == px.PX_ERR_INDEX_OUT_OF_RANGE
     # apply checks the ids it is handed as well
     ids = torch.tensor([1, vocab + 5], dtype=torch.int64, device="cuda")
     rows = torch.ones((2, dim), dtype=torch.float32, device="cuda")
