@@ -99,6 +99,26 @@ class DeviceWorkload:
             b = self.bufs[t][self.step_no % len(self.bufs[t])]
             self.runner.sparse_step(self.ctx, b, self.tables[t], self.accums[t], self.w.optimizer, self.w.lr)
 
+    def sparse_fused(self):
+        """The same work through the fused aggregate-and-apply entry points (then partition)."""
+        for t in range(self.w.n_tables):
+            b = self.bufs[t][self.step_no % len(self.bufs[t])]
+            self.runner.fused_step(self.ctx, b, self.tables[t], self.accums[t], self.w.optimizer, self.w.lr)
+
+    def pull_setup(self):
+        """The pull side: every worker's ids of every table in one batch, rows gathered in batch order."""
+        torch = self.torch
+        self.pull_ids = [torch.cat(self.bufs[t][0].idx) for t in range(self.w.n_tables)]
+        self.pull_out = torch.empty((self.w.total_rows, self.w.dim), dtype=torch.float32, device="cuda")
+
+    def pull(self):
+        for t in range(self.w.n_tables):
+            self.ctx.px_sparse_lookup(self.tables[t], self.pull_ids[t], None, self.w.total_rows, None, None,
+                                      self.pull_out)
+
+    def pull_bytes(self):
+        return self.w.n_tables * self.w.total_rows * (8 + 8 * self.w.dim)
+
     def dense_mean(self):
         if self.dense:
             self.ctx.px_dense_average(self.dense, self.w.dense_count, self.dense_out, 1.0 / self.w.n_workers)
@@ -279,6 +299,21 @@ def main():
         "rows_per_s": rows_per_step / sparse_avg,
     }
 
+    fused_avg, fused_min = event_timed(torch, dw.sparse_fused, max(5, args.steps // 2), 2)
+    result["sparse_chain_fused"] = {
+        "what": "px_sparse_coalesce_apply_* + px_partition_rows: same result, aggregated rows never stored",
+        "avg_us": fused_avg * 1e6, "min_us": fused_min * 1e6,
+        "achieved_gbps_unfused_bytes": sp_bytes / fused_avg / 1e9,
+        "frac_unfused_bytes": sp_bytes / fused_avg / 1e9 / HBM_PEAK_GBPS,
+        "rows_per_s": rows_per_step / fused_avg,
+    }
+    dw.pull_setup()
+    pull_avg, pull_min = event_timed(torch, dw.pull, max(5, args.steps // 2), 2)
+    result["pull_side"] = {
+        "what": "px_sparse_lookup: rows of every worker's ids gathered in batch order, all tables",
+        "avg_us": pull_avg * 1e6, "algorithmic_bytes": dw.pull_bytes(),
+        "achieved_gbps": dw.pull_bytes() / pull_avg / 1e9, "frac": dw.pull_bytes() / pull_avg / 1e9 / HBM_PEAK_GBPS,
+    }
     result["copy_calibration"] = calibration
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(dw)
@@ -300,10 +335,19 @@ def main():
                 odw.sparse()
                 odw.step_no += 1
 
+            def fused_rot(odw=odw):
+                odw.sparse_fused()
+                odw.step_no += 1
+
             s_avg, s_min = event_timed(torch, sparse_rot, 20, 4)
+            f_avg, f_min = event_timed(torch, fused_rot, 20, 4)
             entry = {"unique_rows": odw.unique_counts(), "sparse_avg_us": s_avg * 1e6, "sparse_min_us": s_min * 1e6,
                      "sparse_gbps": obytes / s_avg / 1e9, "sparse_frac": obytes / s_avg / 1e9 / HBM_PEAK_GBPS,
-                     "rows_per_s": ow.n_tables * ow.total_rows / s_avg}
+                     "rows_per_s": ow.n_tables * ow.total_rows / s_avg,
+                     "fused_avg_us": f_avg * 1e6, "fused_frac_unfused_bytes": obytes / f_avg / 1e9 / HBM_PEAK_GBPS}
+            odw.pull_setup()
+            p_avg, _ = event_timed(torch, odw.pull, 10, 2)
+            entry.update({"pull_avg_us": p_avg * 1e6, "pull_frac": odw.pull_bytes() / p_avg / 1e9 / HBM_PEAK_GBPS})
             if odw.dense:
                 d_avg, d_min = event_timed(torch, odw.dense_mean, 10, 2)
                 entry.update({"dense_avg_us": d_avg * 1e6, "dense_gbps": odense / d_avg / 1e9,

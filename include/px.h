@@ -16,6 +16,8 @@
  *   px_dense_average         reduce N workers' dense gradient buffers (sum or mean)
  * and, fused, the first and third of these without the aggregated rows ever being stored:
  *   px_sparse_coalesce_apply_sgd / px_sparse_coalesce_apply_adagrad
+ * and the pull side, the rows of a (partitioned) variable a mini-batch asks for:
+ *   px_sparse_lookup
  *
  * Conventions for every call
  *   - "dev" pointers are device (HBM) addresses on the context's GPU; "host"
@@ -206,6 +208,23 @@ px_status px_sparse_coalesce_apply_adagrad(px_ctx* ctx, int n_workers, const int
  */
 px_status px_dense_average(px_ctx* ctx, int n_buffers, const void* const* bufs, int64_t count,
                            px_dtype in_dtype, void* out, px_dtype out_dtype, float scale,
+                           void* hip_stream);
+
+/*
+ * The pull side of a partitioned sparse variable (Sec. 3.1: workers pull the rows their
+ * mini-batch touches; Sec. 3.2: the rows looked up in the partitions are stitched back into
+ * one tensor in the order of the request):
+ *   out_rows[k][:] = table[ids[k]][:]     for k = perm[j], j in [first, last)
+ *   table    dev float[vocab][dim], read only
+ *   ids      dev int64[cap], any order, may repeat; num_ids dev int64[1] or NULL (= cap)
+ *   perm     dev int32[cap] from px_partition_rows on these ids, or NULL for the identity
+ *   range    dev int64[2] = {first, last} (one shard's slice of perm), or NULL for everything
+ *   out_rows dev float[cap][dim]; only the rows selected by perm / range are written
+ * An id outside [0, vocab) raises the context's flag; its output row is left untouched.
+ */
+px_status px_sparse_lookup(px_ctx* ctx, const float* table, int64_t vocab, int64_t dim,
+                           const int64_t* ids, const int64_t* num_ids, int64_t cap,
+                           const int32_t* perm, const int64_t* range, float* out_rows,
                            void* hip_stream);
 
 #ifdef __cplusplus

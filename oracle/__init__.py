@@ -12,8 +12,8 @@ builds it with g++, loads it with ctypes and marshals numpy arrays.
 Pins (tests/test_oracle_*.py): brute-force densification on tiny inputs,
 column-sum / set-size / disjointness invariants, special cases that are
 bit-exact, integer-valued inputs whose sums are order independent, the first
-Adagrad step's closed form, and PyTorch's CPU sparse-coalesce and sparse
-optimizer routines.
+Adagrad step's closed form, PyTorch's CPU sparse-coalesce and sparse
+optimizer routines, and numpy's fancy indexing for the lookup.
 """
 
 from __future__ import annotations
@@ -63,6 +63,10 @@ def _declare(lib) -> None:
     lib.pxo_sparse_apply_adagrad.argtypes = [
         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
         ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_double, ctypes.c_double]
+    lib.pxo_sparse_lookup.restype = ctypes.c_int
+    lib.pxo_sparse_lookup.argtypes = [
+        ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+        ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p]
     lib.pxo_dense_average.restype = ctypes.c_int
     lib.pxo_dense_average.argtypes = [
         ctypes.c_int, c_pp, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
@@ -186,6 +190,27 @@ def sparse_apply_adagrad(table: np.ndarray, accum: np.ndarray, ids: np.ndarray, 
     _check_apply(lib.pxo_sparse_apply_adagrad(
         table.ctypes.data, accum.ctypes.data, vocab, dim, ids.ctypes.data, rows.ctypes.data,
         ids.size, None if p is None else p.ctypes.data, float(lr), float(eps)))
+
+
+def sparse_lookup(table: np.ndarray, ids: np.ndarray, perm: Optional[np.ndarray] = None,
+                  first: int = 0, last: Optional[int] = None, out: Optional[np.ndarray] = None,
+                  lib=None) -> np.ndarray:
+    """out[k] = table[ids[k]] for k = perm[j], j in [first, last); other rows of out are kept."""
+    lib = lib or load()
+    assert table.dtype == np.float32 and table.flags.c_contiguous
+    vocab, dim = table.shape
+    ids = np.ascontiguousarray(ids, dtype=np.int64)
+    n = ids.size
+    if out is None:
+        out = np.zeros((n, dim), dtype=np.float32)
+    assert out.dtype == np.float32 and out.flags.c_contiguous and out.shape == (n, dim)
+    p = None if perm is None else np.ascontiguousarray(perm, dtype=np.int32)
+    rc = lib.pxo_sparse_lookup(table.ctypes.data, vocab, dim, ids.ctypes.data, n,
+                               None if p is None else p.ctypes.data, first, n if last is None else last,
+                               out.ctypes.data)
+    if rc == 2:
+        raise IdOutOfRange("an id lies outside the table")
+    return out
 
 
 def dense_average(bufs: Sequence[np.ndarray], average: bool = True, lib=None) -> np.ndarray:

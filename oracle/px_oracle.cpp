@@ -166,4 +166,21 @@ int pxo_dense_average(int n_buffers, const void* const* bufs, int64_t count, int
     return 0;
 }
 
+// The pull side of a partitioned sparse variable (Sec. 3.1: a worker pulls the rows its
+// mini-batch touches; Sec. 3.2: rows looked up per partition are stitched into one tensor in
+// the order of the request).  out[k] = table[ids[k]] for k = perm[j], j in [first, last);
+// perm NULL = identity.  Rows outside the range are left as they are.  Returns 2 for a bad id.
+int pxo_sparse_lookup(const float* table, int64_t vocab, int64_t dim, const int64_t* ids, int64_t n,
+                      const int32_t* perm, int64_t first, int64_t last, float* out) {
+    for (int64_t j = first; j < last && j < n; ++j) {
+        int64_t k = perm ? perm[j] : j;
+        if (ids[k] < 0 || ids[k] >= vocab) return 2;
+    }
+    for (int64_t j = first; j < last && j < n; ++j) {
+        int64_t k = perm ? perm[j] : j;
+        for (int64_t d = 0; d < dim; ++d) out[k * dim + d] = table[ids[k] * dim + d];
+    }
+    return 0;
+}
+
 }  // extern "C"

@@ -34,7 +34,7 @@ EXPORTS = [
     "px_create", "px_destroy", "px_status_string", "px_last_error", "px_device_status",
     "px_coalesce_scratch_bytes", "px_partition_scratch_bytes", "px_sparse_coalesce",
     "px_partition_rows", "px_sparse_apply_sgd", "px_sparse_apply_adagrad", "px_dense_average",
-    "px_sparse_coalesce_apply_sgd", "px_sparse_coalesce_apply_adagrad",
+    "px_sparse_coalesce_apply_sgd", "px_sparse_coalesce_apply_adagrad", "px_sparse_lookup",
 ]
 
 if not os.path.exists(LIBRARY):
@@ -72,6 +72,8 @@ lib.px_sparse_coalesce_apply_sgd.argtypes = [_vp, _int, _pp, _pp, _i64p, _i64, _
 lib.px_sparse_coalesce_apply_adagrad.restype = _int
 lib.px_sparse_coalesce_apply_adagrad.argtypes = [_vp, _int, _pp, _pp, _i64p, _i64, _int, _i64, _f32, _vp, _vp,
                                                  _f32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.px_sparse_lookup.restype = _int
+lib.px_sparse_lookup.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp]
 lib.px_partition_rows.restype = _int
 lib.px_partition_rows.argtypes = [_vp, _vp, _vp, _i64, _int, _int, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.px_sparse_apply_sgd.restype = _int
@@ -232,6 +234,16 @@ class Context:
         self._check(lib.px_sparse_apply_adagrad(
             self._h, _ptr(table), _ptr(accum), vocab, dim, _ptr(ids), _ptr(rows), _ptr(num_ids), cap,
             _ptr(perm), _ptr(range_), lr, eps, _stream(stream)))
+
+    def px_sparse_lookup(self, table: torch.Tensor, ids: torch.Tensor, num_ids: Optional[torch.Tensor],
+                         cap: int, perm: Optional[torch.Tensor], range_: Optional[torch.Tensor],
+                         out_rows: torch.Tensor, stream=None) -> None:
+        vocab, dim = table.shape
+        assert table.dtype == torch.float32 and table.is_contiguous()
+        assert out_rows.dtype == torch.float32 and out_rows.is_contiguous() and out_rows.numel() >= cap * dim
+        assert ids.dtype == torch.int64 and ids.is_contiguous() and ids.numel() >= cap
+        self._check(lib.px_sparse_lookup(self._h, _ptr(table), vocab, dim, _ptr(ids), _ptr(num_ids), cap,
+                                         _ptr(perm), _ptr(range_), _ptr(out_rows), _stream(stream)))
 
     def px_dense_average(self, bufs: Sequence[torch.Tensor], count: int, out: torch.Tensor, scale: float,
                          stream=None) -> None:

@@ -419,6 +419,41 @@ def pin_adagrad_torch_library(lib):
     assert np.allclose(accum, opt.state[p]["sum"].numpy(), rtol=1e-6, atol=0)
 
 
+# --------------------------------------------------------------------- lookup
+
+def pin_lookup_is_an_indexed_copy(lib):
+    rng = RNG(16)
+    vocab, dim, n = 90, 5, 400
+    table = rng.standard_normal((vocab, dim), dtype=np.float32)
+    ids = inputs.draw_ids(rng, vocab, 1.1, n)                      # repeats on purpose
+    out = oracle.sparse_lookup(table, ids, lib=lib)
+    assert np.array_equal(out, table[ids])                          # numpy fancy indexing
+    assert np.array_equal(out, np.take(table, ids, axis=0))
+    # shard by shard (the partitioned lookup), stitched by position: same tensor
+    p = 6
+    _, perm, off = oracle.partition_rows(ids, p, "mul", lib=lib)
+    stitched = np.full((n, dim), np.nan, dtype=np.float32)
+    for q in range(p):
+        before = stitched.copy()
+        oracle.sparse_lookup(table, ids, perm=perm, first=int(off[q]), last=int(off[q + 1]), out=stitched, lib=lib)
+        mine = perm[off[q]:off[q + 1]]
+        others = np.setdiff1d(np.arange(n), mine)
+        assert np.array_equal(stitched[others], before[others], equal_nan=True)   # a shard writes only its rows
+        assert np.array_equal(stitched[mine], table[ids[mine]])
+    assert np.array_equal(stitched, out)
+    # the lookup inverts the update's addressing: rows pulled after an SGD step are the updated rows
+    uids, rows, _ = oracle.sparse_coalesce([ids], [rng.standard_normal((n, dim), dtype=np.float32)], dim, vocab, lib=lib)
+    t2 = table.copy()
+    oracle.sparse_apply_sgd(t2, uids, rows, 0.5, lib=lib)
+    assert np.array_equal(oracle.sparse_lookup(t2, uids, lib=lib), t2[uids])
+    try:
+        oracle.sparse_lookup(table, np.array([1, vocab]), lib=lib)
+    except oracle.IdOutOfRange:
+        pass
+    else:
+        raise AssertionError("bad id accepted")
+
+
 # ---------------------------------------------------------------------- dense
 
 def pin_dense_special_cases(lib):

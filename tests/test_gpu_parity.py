@@ -395,6 +395,53 @@ def test_apply_shard_by_shard_equals_apply_all(gpu):
     assert all(((int(c) * 2654435761) % (1 << 64)) % w.n_shards == 2 for c in changed)
 
 
+# -------------------------------------------------------------------- lookup
+
+@pytest.mark.parametrize("dim", [1, 6, 64, 100, 128, 512, 1024, 1300])
+def test_lookup_stitches_shards_in_batch_order(gpu, dim):
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(dim)
+    vocab, n, p = 3000, 5000, 8
+    table = rng.standard_normal((vocab, dim), dtype=np.float32)
+    ids = inputs.draw_ids(rng, vocab, 1.1, n)                         # a batch repeats words
+    d_table, d_ids = torch.from_numpy(table).cuda(), torch.from_numpy(ids).cuda()
+    out = torch.full((n, dim), float("nan"), device="cuda")
+    ctx.px_sparse_lookup(d_table, d_ids, None, n, None, None, out)
+    assert np.array_equal(out.cpu().numpy(), oracle.sparse_lookup(table, ids))
+    # per shard, then stitched: partition the batch ids, pull every shard's rows into place
+    num = torch.tensor([n], dtype=torch.int64, device="cuda")
+    perm = torch.empty(n, dtype=torch.int32, device="cuda")
+    off = torch.empty(p + 1, dtype=torch.int64, device="cuda")
+    ctx.px_partition_rows(d_ids, num, n, p, px.PX_HASH_MUL, None, perm, off,
+                          px.alloc_scratch(px.Context.px_partition_scratch_bytes(n)))
+    o_shard, o_perm, o_off = oracle.partition_rows(ids, p, "mul")
+    assert np.array_equal(perm.cpu().numpy(), o_perm) and np.array_equal(off.cpu().numpy(), o_off)
+    stitched = torch.full((n, dim), float("nan"), device="cuda")
+    ref = np.full((n, dim), np.nan, dtype=np.float32)
+    for q in range(p):
+        ctx.px_sparse_lookup(d_table, d_ids, num, n, perm, off[q:q + 2], stitched)
+        oracle.sparse_lookup(table, ids, perm=o_perm, first=int(o_off[q]), last=int(o_off[q + 1]), out=ref)
+        assert np.array_equal(stitched.cpu().numpy(), ref, equal_nan=True)
+    assert torch.equal(stitched, out)
+    assert ctx.px_device_status() == px.PX_OK
+
+
+def test_lookup_full_size_and_bad_id(gpu):
+    ctx, px, runner = gpu
+    w = inputs.NMT
+    table = inputs.table_init(w)
+    ids = np.concatenate(inputs.sparse_ids(w))                       # all 48 workers' pulls of one table
+    d_table, d_ids = torch.from_numpy(table).cuda(), torch.from_numpy(ids).cuda()
+    out = torch.empty((ids.size, w.dim), device="cuda")
+    ctx.px_sparse_lookup(d_table, d_ids, None, ids.size, None, None, out)
+    assert np.array_equal(out.cpu().numpy(), oracle.sparse_lookup(table, ids))
+    bad = torch.tensor([5, w.vocab, 7], dtype=torch.int64, device="cuda")
+    out3 = torch.full((3, w.dim), -1.0, device="cuda")
+    ctx.px_sparse_lookup(d_table, bad, None, 3, None, None, out3)
+    assert ctx.px_device_status() == px.PX_ERR_INDEX_OUT_OF_RANGE
+    assert torch.equal(out3[0], d_table[5]) and torch.equal(out3[2], d_table[7]) and bool((out3[1] == -1).all())
+
+
 # --------------------------------------------------------------------- dense
 
 @pytest.mark.parametrize("n_buffers,count", [(1, 1000), (4, 65_536), (8, 4099), (48, 70_001), (65, 513),

@@ -41,6 +41,10 @@ MUTANTS = [
     ("adagrad_accumulator_not_stored", "a[d] = (float) ad;", ""),
     ("adagrad_eps_inside_root", "(std::sqrt(ad) + eps)", "std::sqrt(ad + eps)"),
     ("adagrad_sign", "(double) w[d] - lr * gd /", "(double) w[d] + lr * gd /"),
+    ("lookup_wrong_source_row", "out[k * dim + d] = table[ids[k] * dim + d];", "out[k * dim + d] = table[k * dim + d];"),
+    ("lookup_by_visit_order", "out[k * dim + d] = table[ids[k] * dim + d];", "out[j * dim + d] = table[ids[k] * dim + d];"),
+    ("lookup_ignores_range", "for (int64_t j = first; j < last && j < n; ++j) {\n        int64_t k = perm ? perm[j] : j;\n        for",
+     "for (int64_t j = 0; j < n; ++j) {\n        int64_t k = perm ? perm[j] : j;\n        for"),
     ("dense_overwrites", "s += load_value(bufs[w], in_dtype, j);", "s = load_value(bufs[w], in_dtype, j);"),
     ("dense_wrong_divisor", "if (aggregation == AGG_AVERAGE) s /= (double) n_buffers;",
      "if (aggregation == AGG_AVERAGE) s /= (double) (n_buffers - 1);"),
