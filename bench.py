@@ -190,6 +190,42 @@ def event_timed(torch, fn, steps, warmup):
     return float(np.mean(ms)) * 1e-3, float(np.min(ms)) * 1e-3
 
 
+# --------------------------------------------------------- partition search
+
+def partition_search(torch, px, dw, p_start=8, p_max=256):
+    """Sec. 3.2 on this machine: sample the sparse chain's time at the partition counts the paper's
+    rule visits (start at 8, the paper's machine count), fit Eq. 1, report the best count in range."""
+    saved = [(b.n_shards, b.offsets) for t in dw.bufs for b in t]
+
+    def measure(n_shards):
+        for t in dw.bufs:
+            for b in t:
+                b.n_shards = n_shards
+                b.offsets = torch.empty(n_shards + 1, dtype=torch.int64, device="cuda")
+        avg, _ = event_timed(torch, dw.sparse, 30, 10)
+        return avg * 1e6
+
+    ps, ts = [], []
+    while True:
+        nxt = px.px_partition_search_next(ps, ts, p_start, p_max)
+        if nxt == 0:
+            break
+        ps.append(nxt)
+        ts.append(measure(nxt))
+    for extra in (p_start * 2, p_start * 4):            # the fit needs three distinct counts
+        if len(ps) < 3 and extra not in ps and extra <= p_max:
+            ps.append(extra)
+            ts.append(measure(extra))
+    out = {"samples_p": ps, "samples_us": ts}
+    if len(ps) >= 3:
+        theta = px.px_partition_cost_fit(ps, ts)
+        best, when = px.px_partition_cost_argmin(theta, min(ps), max(ps))
+        out.update({"theta": theta, "best_p": best, "predicted_us": when})
+    for (n_shards, offsets), b in zip(saved, [b for t in dw.bufs for b in t]):
+        b.n_shards, b.offsets = n_shards, offsets
+    return out
+
+
 # -------------------------------------------------------------- CPU baseline
 
 def cpu_baseline(dw):
@@ -345,6 +381,8 @@ def main():
                      "sparse_gbps": obytes / s_avg / 1e9, "sparse_frac": obytes / s_avg / 1e9 / HBM_PEAK_GBPS,
                      "rows_per_s": ow.n_tables * ow.total_rows / s_avg,
                      "fused_avg_us": f_avg * 1e6, "fused_frac_unfused_bytes": obytes / f_avg / 1e9 / HBM_PEAK_GBPS}
+            if name == "large_vocab_lm":
+                entry["partition_search"] = partition_search(torch, px, odw)
             odw.pull_setup()
             p_avg, _ = event_timed(torch, odw.pull, 10, 2)
             entry.update({"pull_avg_us": p_avg * 1e6, "pull_frac": odw.pull_bytes() / p_avg / 1e9 / HBM_PEAK_GBPS})

@@ -227,6 +227,26 @@ px_status px_sparse_lookup(px_ctx* ctx, const float* table, int64_t vocab, int64
                            const int32_t* perm, const int64_t* range, float* out_rows,
                            void* hip_stream);
 
+/*
+ * Partition-count cost model (Sec. 3.2, Eq. 1):  iter_time(P) = theta0 + theta1 / P + theta2 * P.
+ * Host-only arithmetic in double; all pointers are host pointers; no context, nothing enqueued.
+ *
+ * px_partition_cost_fit      least-squares fit of theta[3] to n >= 3 samples (p[i] > 0, at least three
+ *                            distinct values; PX_ERR_INVALID_ARG otherwise).
+ * px_partition_cost_argmin   the integer P in [p_lo, p_hi] with the smallest fitted time (Eq. 1 is
+ *                            convex for theta1, theta2 > 0 with critical point sqrt(theta1/theta2));
+ *                            best_time may be NULL.
+ * px_partition_search_next   the paper's sampling rule: start at p_start, double while the time does
+ *                            not go up (never beyond p_max), then halve from p_start while it does not
+ *                            go up.  Given the samples taken so far it returns the next P to measure
+ *                            in *next_p, or 0 once sampling is complete.
+ */
+px_status px_partition_cost_fit(const double* p, const double* t, int n, double* theta);
+px_status px_partition_cost_argmin(const double* theta, int64_t p_lo, int64_t p_hi, int64_t* best_p,
+                                   double* best_time);
+px_status px_partition_search_next(const double* p, const double* t, int n, int64_t p_start,
+                                   int64_t p_max, int64_t* next_p);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIBRARY = os.path.join(HERE, "libpx.so")
-SOURCES = ["px_core.hip", "px_coalesce.hip", "px_partition.hip", "px_apply.hip", "px_dense.hip", "px_lookup.hip"]
+SOURCES = ["px_core.hip", "px_coalesce.hip", "px_partition.hip", "px_apply.hip", "px_dense.hip", "px_lookup.hip", "px_costmodel.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

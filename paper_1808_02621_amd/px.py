@@ -35,6 +35,7 @@ EXPORTS = [
     "px_coalesce_scratch_bytes", "px_partition_scratch_bytes", "px_sparse_coalesce",
     "px_partition_rows", "px_sparse_apply_sgd", "px_sparse_apply_adagrad", "px_dense_average",
     "px_sparse_coalesce_apply_sgd", "px_sparse_coalesce_apply_adagrad", "px_sparse_lookup",
+    "px_partition_cost_fit", "px_partition_cost_argmin", "px_partition_search_next",
 ]
 
 if not os.path.exists(LIBRARY):
@@ -83,6 +84,15 @@ lib.px_sparse_apply_adagrad.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp
                                         _f32, _vp]
 lib.px_dense_average.restype = _int
 lib.px_dense_average.argtypes = [_vp, _int, _pp, _i64, _int, _vp, _int, _f32, _vp]
+
+
+_dp = ctypes.POINTER(ctypes.c_double)
+lib.px_partition_cost_fit.restype = _int
+lib.px_partition_cost_fit.argtypes = [_dp, _dp, _int, _dp]
+lib.px_partition_cost_argmin.restype = _int
+lib.px_partition_cost_argmin.argtypes = [_dp, _i64, _i64, _i64p, _dp]
+lib.px_partition_search_next.restype = _int
+lib.px_partition_search_next.argtypes = [_dp, _dp, _int, _i64, _i64, _i64p]
 
 
 class PxError(RuntimeError):
@@ -255,6 +265,35 @@ class Context:
         assert out.is_contiguous() and out.numel() >= count
         self._check(lib.px_dense_average(self._h, n, _ptr_array(bufs), count, code, _ptr(out),
                                          _dtype_code(out), scale, _stream(stream)))
+
+
+def _doubles(values):
+    return (ctypes.c_double * max(1, len(values)))(*[float(v) for v in values])
+
+
+def px_partition_cost_fit(p: Sequence[float], t: Sequence[float]):
+    """theta of Eq. 1 fitted to the samples (host arithmetic)."""
+    theta = (ctypes.c_double * 3)()
+    rc = lib.px_partition_cost_fit(_doubles(p), _doubles(t), len(p), theta)
+    if rc != PX_OK:
+        raise PxError(rc, "cost model fit needs three distinct positive partition counts")
+    return [theta[0], theta[1], theta[2]]
+
+
+def px_partition_cost_argmin(theta: Sequence[float], p_lo: int, p_hi: int):
+    best, when = ctypes.c_int64(), ctypes.c_double()
+    rc = lib.px_partition_cost_argmin(_doubles(theta), p_lo, p_hi, ctypes.byref(best), ctypes.byref(when))
+    if rc != PX_OK:
+        raise PxError(rc, "bad range")
+    return best.value, when.value
+
+
+def px_partition_search_next(p: Sequence[float], t: Sequence[float], p_start: int, p_max: int) -> int:
+    nxt = ctypes.c_int64()
+    rc = lib.px_partition_search_next(_doubles(p), _doubles(t), len(p), p_start, p_max, ctypes.byref(nxt))
+    if rc != PX_OK:
+        raise PxError(rc, "bad search arguments")
+    return nxt.value
 
 
 def alloc_scratch(nbytes: int, device="cuda") -> torch.Tensor:
