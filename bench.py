@@ -383,6 +383,20 @@ def main():
                      "fused_avg_us": f_avg * 1e6, "fused_frac_unfused_bytes": obytes / f_avg / 1e9 / HBM_PEAK_GBPS}
             if name == "large_vocab_lm":
                 entry["partition_search"] = partition_search(torch, px, odw)
+                b0 = odw.bufs[0][0]
+
+                def two_level(b0=b0, ow=ow):
+                    odw.runner.two_level_coalesce(ctx, b0.idx, b0.val, ow.dim, ow.vocab, 6)
+
+                def one_level(b0=b0):
+                    odw.runner.coalesce(ctx, b0)
+
+                t2, _ = event_timed(torch, two_level, 10, 2)
+                t1, _ = event_timed(torch, one_level, 10, 2)
+                entry["two_level_aggregation"] = {
+                    "what": "coalesce per group of 6 workers, read the 8 counts back, coalesce the 8 results "
+                            "(allocations included) vs one coalesce of all 48",
+                    "two_level_us": t2 * 1e6, "one_level_us": t1 * 1e6}
             odw.pull_setup()
             p_avg, _ = event_timed(torch, odw.pull, 10, 2)
             entry.update({"pull_avg_us": p_avg * 1e6, "pull_frac": odw.pull_bytes() / p_avg / 1e9 / HBM_PEAK_GBPS})

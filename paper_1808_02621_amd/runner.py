@@ -107,3 +107,21 @@ def fused_step(ctx: px.Context, b: SparseBuffers, table: torch.Tensor, accum: Op
     else:
         raise ValueError(optimizer)
     partition(ctx, b, stream)
+
+
+def two_level_coalesce(ctx: px.Context, idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], dim: int,
+                       vocab: int, group: int, stream=None):
+    """Aggregation in two levels (Parallax Sec. 4.3): first among the `group` workers of each machine,
+    then across machines.  Returns the second level's SparseBuffers (ids, rows, count) and the list
+    of first-level buffers.  The first-level counts are read back to the host in between (one
+    synchronisation), because the second call takes its row counts from the host."""
+    firsts = []
+    for g0 in range(0, len(idx), group):
+        b = sparse_buffers(idx[g0:g0 + group], val[g0:g0 + group], dim, vocab, 1, px.PX_HASH_MOD)
+        coalesce(ctx, b, 1.0, stream)
+        firsts.append(b)
+    counts = torch.cat([b.out_num for b in firsts]).cpu().tolist()
+    second = sparse_buffers([b.out_ids[:n] for b, n in zip(firsts, counts)],
+                            [b.out_rows[:n] for b, n in zip(firsts, counts)], dim, vocab, 1, px.PX_HASH_MOD)
+    coalesce(ctx, second, 1.0, stream)
+    return second, firsts

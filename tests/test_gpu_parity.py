@@ -344,6 +344,35 @@ def test_host_side_argument_errors(gpu):
     assert e.value.status == px.PX_ERR_INVALID_ARG
 
 
+def test_two_level_aggregation(gpu):
+    """Local aggregation per machine, then global (Sec. 4.3): 8 groups of 6 workers, as in the paper's
+    cluster.  Same ids; rows equal the one-level result up to the float rounding of the group sums,
+    and equal the oracle run the same two-level way to the last bit or so."""
+    ctx, px, runner = gpu
+    w = inputs.shrink(inputs.LARGE_LM, vocab=60_000, n_per_worker=700)
+    idx, val = inputs.sparse_ids(w), inputs.sparse_values(w)
+    d_idx = [runner.to_device(i) for i in idx]
+    d_val = [runner.to_device(v) for v in val]
+    second, firsts = runner.two_level_coalesce(ctx, d_idx, d_val, w.dim, w.vocab, 6)
+    assert len(firsts) == 8 and ctx.px_device_status() == px.PX_OK
+    u = int(second.out_num.item())
+    o_ids, o_rows, _ = oracle.sparse_coalesce(idx, val, w.dim, w.vocab)
+    assert u == o_ids.size and np.array_equal(second.out_ids[:u].cpu().numpy(), o_ids)
+    # against the one-level sum: each of the 8 group sums was rounded to float (half an ulp of a value
+    # of magnitude up to ~100, i.e. ~4e-6) before the second level, so sums that cancel keep that error
+    close(second.out_rows[:u].cpu().numpy(), o_rows, abs_=8 * 4e-6)
+    gi, gv = [], []
+    for g in range(8):
+        a, b, _ = oracle.sparse_coalesce(idx[6 * g:6 * g + 6], val[6 * g:6 * g + 6], w.dim, w.vocab)
+        gi.append(a)
+        gv.append(b)
+        n = int(firsts[g].out_num.item())
+        assert np.array_equal(firsts[g].out_ids[:n].cpu().numpy(), a)
+    t_ids, t_rows, _ = oracle.sparse_coalesce(gi, gv, w.dim, w.vocab)
+    x, ref = second.out_rows[:u].cpu().numpy(), t_rows
+    assert np.all(np.abs(x - ref) <= 2 * np.spacing(np.abs(ref)))
+
+
 # ---------------------------------------------------------------- partition
 
 @pytest.mark.parametrize("n_shards", [1, 2, 3, 7, 16, 100, 256])
