@@ -218,6 +218,23 @@ def test_ragged_workers_with_an_empty_one(gpu):
     run_chain(gpu, idx, val, dim, vocab, 7, "mod", "sgd", 1.0, table)
 
 
+def test_most_workers_allowed(gpu):
+    """PX_MAX_SOURCES workers (the pointer tables take several uploads), a few rows each."""
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(44)
+    dim, vocab, n = 16, 700, px.PX_MAX_SOURCES
+    sizes = rng.integers(0, 6, size=n)
+    idx = [rng.integers(0, vocab, size=int(k), dtype=np.int64) for k in sizes]
+    val = [rng.standard_normal((int(k), dim), dtype=np.float32) for k in sizes]
+    table = np.zeros((vocab, dim), dtype=np.float32)
+    run_chain(gpu, idx, val, dim, vocab, 16, "mul", "sgd", 0.3, table)
+    with pytest.raises(px.PxError) as e:
+        b = runner.sparse_buffers([runner.to_device(idx[0])] * (n + 1), [runner.to_device(val[0])] * (n + 1), dim,
+                                  vocab, 2, px.PX_HASH_MOD)
+        runner.coalesce(ctx, b)
+    assert e.value.status == px.PX_ERR_INVALID_ARG
+
+
 def test_single_worker_all_distinct_is_a_permutation(gpu):
     rng = np.random.default_rng(5)
     dim, vocab = 48, 6000
