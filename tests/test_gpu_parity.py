@@ -390,6 +390,77 @@ def test_two_level_aggregation(gpu):
     assert np.all(np.abs(x - ref) <= 2 * np.spacing(np.abs(ref)))
 
 
+def test_whole_path_replays_from_a_hip_graph(gpu):
+    """The calls only enqueue kernels (no allocation, no memset, no host staging), so the whole path can
+    be captured once and replayed; every replay, with fresh inputs written into the same buffers and
+    eager work in between, must give the eager result."""
+    ctx, px, runner = gpu
+    w = inputs.shrink(inputs.LARGE_LM, vocab=30_000, n_workers=8, n_per_worker=1500, dim=128, dense_count=50_000)
+    rng = np.random.default_rng(77)
+
+    def fresh():
+        idx = [inputs.draw_ids(rng, w.vocab, 1.0, w.n_per_worker) for _ in range(w.n_workers)]
+        val = [rng.standard_normal((w.n_per_worker, w.dim), dtype=np.float32) for _ in range(w.n_workers)]
+        dense = [rng.standard_normal(w.dense_count, dtype=np.float32) for _ in range(w.n_workers)]
+        return idx, val, dense
+
+    idx, val, dense = fresh()
+    d_idx = [runner.to_device(i) for i in idx]
+    d_val = [runner.to_device(v) for v in val]
+    d_dense = [runner.to_device(x) for x in dense]
+    b = runner.sparse_buffers(d_idx, d_val, w.dim, w.vocab, w.n_shards, px.PX_HASH_MUL)
+    table0 = torch.from_numpy(inputs.table_init(w)).cuda()
+    accum0 = torch.from_numpy(inputs.accum_init(w)).cuda()
+    table, accum = table0.clone(), accum0.clone()
+    f_table, f_accum = table0.clone(), accum0.clone()
+    dense_out = torch.empty(w.dense_count, dtype=torch.float32, device="cuda")
+    pulled = torch.empty((w.total_rows, w.dim), dtype=torch.float32, device="cuda")
+    all_ids = torch.cat(d_idx)
+
+    def whole_path(t, a):
+        runner.sparse_step(ctx, b, t, a, "adagrad", w.lr)
+        ctx.px_dense_average(d_dense, w.dense_count, dense_out, 1.0 / w.n_workers)
+        ctx.px_sparse_lookup(t, all_ids, None, w.total_rows, None, None, pulled)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        whole_path(table, accum)                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    table.copy_(table0)
+    accum.copy_(accum0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        whole_path(table, accum)
+    table.copy_(table0)                                            # capture does not run anything
+    accum.copy_(accum0)
+
+    for replay in range(4):
+        if replay:
+            idx, val, dense = fresh()
+            for dst, src in zip(d_idx, idx):
+                dst.copy_(torch.from_numpy(src))
+            for dst, src in zip(d_val, val):
+                dst.copy_(torch.from_numpy(src))
+            for dst, src in zip(d_dense, dense):
+                dst.copy_(torch.from_numpy(src))
+            all_ids.copy_(torch.cat(d_idx))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (table.clone(), accum.clone(), dense_out.clone(), pulled.clone(), b.out_ids.clone(), int(b.out_num.item()))
+        whole_path(f_table, f_accum)                               # the same step, eagerly, on the twin state
+        torch.cuda.synchronize()
+        assert ctx.px_device_status() == px.PX_OK
+        u = int(b.out_num.item())
+        assert got[5] == u and torch.equal(got[4][:u], b.out_ids[:u])
+        assert torch.equal(got[0], f_table) and torch.equal(got[1], f_accum)
+        assert torch.equal(got[2], dense_out) and torch.equal(got[3], pulled)
+    ref_ids, _, _ = oracle.sparse_coalesce(idx, val, w.dim, w.vocab)
+    assert np.array_equal(b.out_ids[:u].cpu().numpy(), ref_ids)
+    assert not torch.equal(f_table, table0)
+
+
 # ---------------------------------------------------------------- partition
 
 @pytest.mark.parametrize("n_shards", [1, 2, 3, 7, 16, 100, 256])
