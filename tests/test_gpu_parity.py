@@ -169,6 +169,30 @@ def test_row_widths(gpu, dim, bf16):
     run_chain(gpu, idx, val, dim, vocab, 3, "mul", "adagrad", 0.1, table, accum)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(gpu, seed):
+    """Random worker counts, ragged sizes, widths, vocabularies, skews, shard counts and optimizers."""
+    rng = np.random.default_rng(1000 + seed)
+    n_workers = int(rng.integers(1, 70))
+    vocab = int(rng.choice([1, 2, 37, 500, 4096, 70_000, 1 << 20]))
+    dim = int(rng.choice([1, 4, 5, 16, 36, 64, 96, 128, 200, 256, 384, 520, 1024]))
+    budget = int(rng.choice([300, 5000, 60_000])) if dim <= 256 else int(rng.choice([300, 5000]))
+    skew = rng.choice([None, 0.8, 1.0, 1.5, 2.5])
+    sizes = rng.multinomial(budget, rng.dirichlet(np.ones(n_workers) * 0.5))
+    idx = [inputs.draw_ids(rng, vocab, None if skew is None else float(skew), int(k)) for k in sizes]
+    bf16 = bool(rng.integers(0, 2))
+    val = [rng.standard_normal((int(k), dim), dtype=np.float32) for k in sizes]
+    if bf16:
+        val = [inputs.f32_to_bf16_bits(v) for v in val]
+    table = (rng.standard_normal((vocab, dim)) * 0.02).astype(np.float32)
+    optimizer = str(rng.choice(["sgd", "adagrad"]))
+    accum = np.full((vocab, dim), 0.1, dtype=np.float32) if optimizer == "adagrad" else None
+    n_shards = int(rng.choice([1, 2, 3, 8, 16, 31, 256]))
+    scale = float(rng.choice([1.0, 1.0 / n_workers]))
+    run_chain(gpu, idx, val, dim, vocab, n_shards, str(rng.choice(["mod", "mul"])), optimizer,
+              float(rng.choice([0.01, 0.5])), table, accum, scale=scale)
+
+
 def test_unaligned_value_pointers(gpu):
     """Value rows that start 4 bytes into an allocation take the element-wise path."""
     ctx, px, runner = gpu
