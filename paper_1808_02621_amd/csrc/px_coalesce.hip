@@ -17,6 +17,8 @@
 //   5. fixup   each split run adds up its partial rows, rounds once, writes its row
 // Nothing waits on another workgroup and global atomics only append to the list of split
 // runs, so the sums are deterministic.
+#include <string.h>
+
 #include <type_traits>
 
 #include "px_radix.h"
@@ -140,18 +142,33 @@ __device__ __forceinline__ uint32_t key_of(uint64_t w) { return (uint32_t) (w >>
 
 // ---------------------------------------------------------------------- pack
 
-__global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(const uint64_t* __restrict__ words,
+// The per-worker tables [idx pointers | value pointers | row prefix] come either from the context's
+// device table (words) or, when they fit, inside the launch arguments (pack, CARRIED): then block 0
+// also stores them to the device table for the kernels that follow and clears the counters, and
+// the separate upload launch is saved.
+template <bool CARRIED>
+__global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__ words, px_word_pack pack,
+                                                          uint32_t* __restrict__ counters, int n_counters,
                                                           int n_workers, int64_t m, int64_t vocab,
                                                           int local_bits, uint64_t* __restrict__ keys,
                                                           uint32_t* __restrict__ hist, int64_t chunk,
                                                           uint32_t* __restrict__ flags) {
     __shared__ uint32_t s_prefix[PX_MAX_SOURCES + 1];
+    __shared__ uint64_t s_idx[CARRIED ? PX_UPLOAD_WORDS / 3 + 1 : 1];
     __shared__ uint32_t s_hist[PX_RADIX];
     const int tid = threadIdx.x;
-    for (int i = tid; i <= n_workers; i += PX_SORT_THREADS) s_prefix[i] = (uint32_t) words[2 * n_workers + i];
+    if (CARRIED) {
+        for (int i = tid; i <= n_workers; i += PX_SORT_THREADS) s_prefix[i] = (uint32_t) pack.w[2 * n_workers + i];
+        for (int i = tid; i < n_workers; i += PX_SORT_THREADS) s_idx[i] = pack.w[i];
+        if (blockIdx.x == 0) {
+            for (int i = tid; i < 3 * n_workers + 1; i += PX_SORT_THREADS) words[i] = pack.w[i];
+            for (int i = tid; i < n_counters; i += PX_SORT_THREADS) counters[i] = 0u;
+        }
+    } else {
+        for (int i = tid; i <= n_workers; i += PX_SORT_THREADS) s_prefix[i] = (uint32_t) words[2 * n_workers + i];
+    }
     s_hist[tid] = 0u;
     __syncthreads();
-    const int64_t* const* idx = (const int64_t* const*) words;
     const int64_t begin = (int64_t) blockIdx.x * chunk;
     int64_t end = begin + chunk;
     if (end > m) end = m;
@@ -162,7 +179,8 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(const uint64_t* __rest
             if ((int64_t) s_prefix[mid] <= p) lo = mid; else hi = mid;
         }
         const uint32_t local = (uint32_t) (p - (int64_t) s_prefix[lo]);
-        int64_t id = idx[lo][local];
+        const int64_t* ids = (const int64_t*) (CARRIED ? s_idx[lo] : words[lo]);
+        int64_t id = ids[local];
         if (id < 0 || id >= vocab) {
             atomicOr(flags, (uint32_t) PXF_BAD_ID);
             id = 0;
@@ -894,13 +912,21 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
         run += counts[w];
     }
     host_words[3 * n_workers] = (uint64_t) run;
-    // one launch for N <= 85 workers: [idx pointers | value pointers | row prefix]
-    px_status st = px_upload_words(ctx, ctx->d_words, host_words, 3 * n_workers + 1, sc.counters, 64, stream);
-    if (st != PX_OK) return st;
-
     const px_sort_geom g = px_sort_geometry(m);
-    k_pack<<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, n_workers, m, vocab, local_bits,
-                                                       sc.keys_a, sc.hist, g.chunk, ctx->d_flags);
+    if (3 * n_workers + 1 <= PX_UPLOAD_WORDS) {
+        // up to 85 workers: the tables ride in the pack kernel's own arguments
+        px_word_pack pack;
+        memcpy(pack.w, host_words, (size_t) (3 * n_workers + 1) * sizeof(uint64_t));
+        k_pack<true><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, pack, sc.counters, 64, n_workers, m, vocab,
+                                                                 local_bits, sc.keys_a, sc.hist, g.chunk, ctx->d_flags);
+    } else {
+        px_status st = px_upload_words(ctx, ctx->d_words, host_words, 3 * n_workers + 1, sc.counters, 64, stream);
+        if (st != PX_OK) return st;
+        px_word_pack unused;
+        unused.w[0] = 0;
+        k_pack<false><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, unused, sc.counters, 64, n_workers, m, vocab,
+                                                                  local_bits, sc.keys_a, sc.hist, g.chunk, ctx->d_flags);
+    }
     int key_bits = bits_for((uint64_t) (vocab - 1));
     int passes = (key_bits + 7) / 8;
     if (passes < 1) passes = 1;

@@ -23,11 +23,6 @@ px_status px_check_hip(px_ctx* ctx, hipError_t e, const char* what) {
 // ------------------------------------------------------------------- upload
 // Up to PX_UPLOAD_WORDS words travel inside the kernel arguments, so the copy is
 // ordered with the stream, needs no pinned staging buffer and can be captured.
-enum { PX_UPLOAD_WORDS = 256 };
-struct px_word_pack {
-    uint64_t w[PX_UPLOAD_WORDS];
-};
-
 __global__ __launch_bounds__(256) void px_k_upload(uint64_t* __restrict__ dst, px_word_pack pack,
                                                    int n, uint32_t* __restrict__ zero, int nzero) {
     int t = threadIdx.x;

@@ -25,6 +25,12 @@ enum { PXF_BAD_ID = 1u };                   // bits of d_flags[0]
 px_status px_fail(px_ctx* ctx, px_status s, const char* fmt, ...);
 px_status px_check_hip(px_ctx* ctx, hipError_t e, const char* what);
 
+// Up to PX_UPLOAD_WORDS 64-bit words can ride inside the arguments of a kernel launch.
+enum { PX_UPLOAD_WORDS = 256 };
+struct px_word_pack {
+    uint64_t w[PX_UPLOAD_WORDS];
+};
+
 // Copies `n` host words into device memory at `dst` through kernel arguments
 // (no host staging buffer, safe to capture), and zeroes `nzero` 32-bit words at `zero`.
 px_status px_upload_words(px_ctx* ctx, uint64_t* dst, const uint64_t* host_words, int n,
