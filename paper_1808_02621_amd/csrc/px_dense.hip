@@ -5,6 +5,8 @@
 // on the slice it owns.  One streaming pass: each thread owns 16 bytes of every
 // input buffer (4 floats or 8 bfloat16), keeps 8 loads in flight, adds in worker
 // order and writes once.  Pure HBM streaming: N*C*es bytes in, C*4 (or C*2) out.
+#include <string.h>
+
 #include "px_internal.h"
 
 namespace {
@@ -65,13 +67,16 @@ template <> struct In<uint16_t> {
 };
 
 // Thread i owns piece i (16 bytes) of every buffer.
-template <typename TIN, bool OUT_BF16>
-__global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ words, int n_buffers,
-                                                   int64_t pieces, void* __restrict__ out, float scale) {
+// The buffer pointers come from the context's device table (words) or, for up to PX_UPLOAD_WORDS
+// buffers, inside the launch arguments (pack, CARRIED), which saves the upload launch.
+template <typename TIN, bool OUT_BF16, bool CARRIED>
+__global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ words, px_word_pack pack,
+                                                   int n_buffers, int64_t pieces, void* __restrict__ out,
+                                                   float scale) {
     enum { E = In<TIN>::E };
     const int64_t i = (int64_t) blockIdx.x * 256 + threadIdx.x;
     if (i >= pieces) return;
-    const uint4* const* bufs = (const uint4* const*) words;
+    const uint4* const* bufs = (const uint4* const*) (CARRIED ? pack.w : words);
     acc_t acc[E];
 #pragma unroll
     for (int x = 0; x < E; ++x) acc[x] = (acc_t) 0;
@@ -110,13 +115,13 @@ __global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ 
 }
 
 // One element per thread, for unaligned buffers and for the tail behind the last full piece.
-template <typename TIN, bool OUT_BF16>
-__global__ __launch_bounds__(256) void k_dense_scalar(const uint64_t* __restrict__ words, int n_buffers,
-                                                      int64_t first, int64_t count, void* __restrict__ out,
-                                                      float scale) {
+template <typename TIN, bool OUT_BF16, bool CARRIED>
+__global__ __launch_bounds__(256) void k_dense_scalar(const uint64_t* __restrict__ words, px_word_pack pack,
+                                                      int n_buffers, int64_t first, int64_t count,
+                                                      void* __restrict__ out, float scale) {
     const int64_t i = first + (int64_t) blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
-    const TIN* const* bufs = (const TIN* const*) words;
+    const TIN* const* bufs = (const TIN* const*) (CARRIED ? pack.w : words);
     acc_t acc = (acc_t) 0;
     for (int w = 0; w < n_buffers; ++w) acc += (acc_t) In<TIN>::widen(bufs[w][i]);
     const float o = (float) (acc * (acc_t) scale);
@@ -124,18 +129,33 @@ __global__ __launch_bounds__(256) void k_dense_scalar(const uint64_t* __restrict
     else ((float*) out)[i] = o;
 }
 
-template <typename TIN, bool OUT_BF16>
-void launch(px_ctx* ctx, int n, int64_t count, bool vec, void* out, float scale, hipStream_t stream) {
+template <typename TIN, bool OUT_BF16, bool CARRIED>
+void launch(px_ctx* ctx, const px_word_pack& pack, int n, int64_t count, bool vec, void* out, float scale,
+            hipStream_t stream) {
     enum { E = In<TIN>::E };
     int64_t done = 0;
     if (vec) {
         const int64_t pieces = count / E;
         if (pieces > 0)
-            k_dense_vec<TIN, OUT_BF16><<<(unsigned) ((pieces + 255) / 256), 256, 0, stream>>>(ctx->d_words, n, pieces, out, scale);
+            k_dense_vec<TIN, OUT_BF16, CARRIED><<<(unsigned) ((pieces + 255) / 256), 256, 0, stream>>>(
+                ctx->d_words, pack, n, pieces, out, scale);
         done = pieces * E;
     }
     if (done < count)
-        k_dense_scalar<TIN, OUT_BF16><<<(unsigned) ((count - done + 255) / 256), 256, 0, stream>>>(ctx->d_words, n, done, count, out, scale);
+        k_dense_scalar<TIN, OUT_BF16, CARRIED><<<(unsigned) ((count - done + 255) / 256), 256, 0, stream>>>(
+            ctx->d_words, pack, n, done, count, out, scale);
+}
+
+template <bool CARRIED>
+void launch_dtype(px_ctx* ctx, const px_word_pack& pack, int n, int64_t count, bool vec, px_dtype in_dtype,
+                  void* out, px_dtype out_dtype, float scale, hipStream_t stream) {
+    if (in_dtype == PX_F32) {
+        if (out_dtype == PX_F32) launch<float, false, CARRIED>(ctx, pack, n, count, vec, out, scale, stream);
+        else launch<float, true, CARRIED>(ctx, pack, n, count, vec, out, scale, stream);
+    } else {
+        if (out_dtype == PX_F32) launch<uint16_t, false, CARRIED>(ctx, pack, n, count, vec, out, scale, stream);
+        else launch<uint16_t, true, CARRIED>(ctx, pack, n, count, vec, out, scale, stream);
+    }
 }
 
 }  // namespace
@@ -161,14 +181,15 @@ extern "C" px_status px_dense_average(px_ctx* ctx, int n_buffers, const void* co
         if (((uintptr_t) bufs[w]) % 16) vec = false;
         host_words[w] = (uint64_t) (uintptr_t) bufs[w];
     }
-    px_status st = px_upload_words(ctx, ctx->d_words, host_words, n_buffers, nullptr, 0, stream);
-    if (st != PX_OK) return st;
-    if (in_dtype == PX_F32) {
-        if (out_dtype == PX_F32) launch<float, false>(ctx, n_buffers, count, vec, out, scale, stream);
-        else launch<float, true>(ctx, n_buffers, count, vec, out, scale, stream);
+    px_word_pack pack;
+    if (n_buffers <= PX_UPLOAD_WORDS) {
+        memcpy(pack.w, host_words, (size_t) n_buffers * sizeof(uint64_t));
+        launch_dtype<true>(ctx, pack, n_buffers, count, vec, in_dtype, out, out_dtype, scale, stream);
     } else {
-        if (out_dtype == PX_F32) launch<uint16_t, false>(ctx, n_buffers, count, vec, out, scale, stream);
-        else launch<uint16_t, true>(ctx, n_buffers, count, vec, out, scale, stream);
+        px_status st = px_upload_words(ctx, ctx->d_words, host_words, n_buffers, nullptr, 0, stream);
+        if (st != PX_OK) return st;
+        pack.w[0] = 0;
+        launch_dtype<false>(ctx, pack, n_buffers, count, vec, in_dtype, out, out_dtype, scale, stream);
     }
     return px_check_hip(ctx, hipGetLastError(), "dense launch");
 }
