@@ -322,11 +322,16 @@ def main():
     if dense_pairs:
         ms = [a.elapsed_time(b) for a, b in dense_pairs]
         avg = float(np.mean(ms)) * 1e-3
+        # px_dense_average cuts an output above 32 MiB into launches of 8 MiB of output each
+        out_bytes = w.dense_count * 4
+        launches = -(-out_bytes // (8 << 20)) if out_bytes > (32 << 20) else 1
+        traffic = measured_traffic("k_dense_vec", w.name)
         result["roofline"] = {
-            "kernel": "k_dense_vec (px_dense_average)", "bound": "hbm",
+            "kernel": "k_dense_vec (px_dense_average, %d launches per call)" % launches, "bound": "hbm",
             "achieved": dn_bytes / avg / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": dn_bytes / avg / 1e9 / HBM_PEAK_GBPS, "traffic": measured_traffic("k_dense_vec", w.name),
-            "avg_launch_us": avg * 1e6, "algorithmic_bytes_per_launch": dn_bytes,
+            "frac": dn_bytes / avg / 1e9 / HBM_PEAK_GBPS, "traffic": traffic,
+            "launches_per_call": launches, "avg_call_us": avg * 1e6,
+            "avg_launch_us": avg * 1e6 / launches, "algorithmic_bytes_per_launch": dn_bytes // launches,
         }
     sparse_avg, sparse_min = event_timed(torch, dw.sparse, max(5, args.steps // 2), 2)
     result["sparse_chain"] = {

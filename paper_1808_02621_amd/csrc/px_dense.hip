@@ -67,14 +67,19 @@ template <> struct In<uint16_t> {
 };
 
 // Thread i owns piece i (16 bytes) of every buffer.
+#ifndef PX_DENSE_CHUNK_MB
+#define PX_DENSE_CHUNK_MB 8     // output bytes per launch, in MiB (0: one launch for everything)
+#endif
+
 // The buffer pointers come from the context's device table (words) or, for up to PX_UPLOAD_WORDS
 // buffers, inside the launch arguments (pack, CARRIED), which saves the upload launch.
+// One launch covers pieces [first, pieces).
 template <typename TIN, bool OUT_BF16, bool CARRIED>
 __global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ words, px_word_pack pack,
-                                                   int n_buffers, int64_t pieces, void* __restrict__ out,
-                                                   float scale) {
+                                                   int n_buffers, int64_t first, int64_t pieces,
+                                                   void* __restrict__ out, float scale) {
     enum { E = In<TIN>::E };
-    const int64_t i = (int64_t) blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = first + (int64_t) blockIdx.x * 256 + threadIdx.x;
     if (i >= pieces) return;
     const uint4* const* bufs = (const uint4* const*) (CARRIED ? pack.w : words);
     acc_t acc[E];
@@ -135,10 +140,19 @@ void launch(px_ctx* ctx, const px_word_pack& pack, int n, int64_t count, bool ve
     enum { E = In<TIN>::E };
     int64_t done = 0;
     if (vec) {
+        // A long output is produced by several launches in a row, each small enough for its output
+        // to stay in the L2 caches until the launch ends and is written back in one burst: a steady
+        // trickle of writes between the reads costs this machine more than the extra launches do.
         const int64_t pieces = count / E;
-        if (pieces > 0)
-            k_dense_vec<TIN, OUT_BF16, CARRIED><<<(unsigned) ((pieces + 255) / 256), 256, 0, stream>>>(
-                ctx->d_words, pack, n, pieces, out, scale);
+        const int64_t out_piece_bytes = E * (OUT_BF16 ? 2 : 4);
+        int64_t per_launch = pieces;
+        if (PX_DENSE_CHUNK_MB > 0 && pieces * out_piece_bytes > 4 * ((int64_t) PX_DENSE_CHUNK_MB << 20))
+            per_launch = ((int64_t) PX_DENSE_CHUNK_MB << 20) / out_piece_bytes;     // measured: 8 MiB best of 4..16
+        for (int64_t first = 0; first < pieces; first += per_launch) {
+            const int64_t last = first + per_launch < pieces ? first + per_launch : pieces;
+            k_dense_vec<TIN, OUT_BF16, CARRIED><<<(unsigned) ((last - first + 255) / 256), 256, 0, stream>>>(
+                ctx->d_words, pack, n, first, last, out, scale);
+        }
         done = pieces * E;
     }
     if (done < count)
