@@ -313,10 +313,13 @@ __global__ void k_write_zero_count(int64_t* out_num_unique) {
 #define PX_SEG_ACC double       // accumulator type of the segmented sum
 #endif
 #ifndef PX_SEG_ROWS
-#define PX_SEG_ROWS 8           // rows in flight per lane group (up to two pieces per lane)
+#define PX_SEG_ROWS 8           // rows per batch and lane group, one piece per lane (two batches are in flight)
+#endif
+#ifndef PX_SEG_ROWS_2
+#define PX_SEG_ROWS_2 4         // two pieces per lane
 #endif
 #ifndef PX_SEG_ROWS_WIDE
-#define PX_SEG_ROWS_WIDE 4      // rows in flight per lane group (four pieces per lane)
+#define PX_SEG_ROWS_WIDE 2      // four pieces per lane
 #endif
 typedef PX_SEG_ACC seg_acc_t;
 
@@ -536,78 +539,113 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
     };
 
     if (active) {
-        for (int64_t r = s; r < e; r += B) {
-            uint64_t w[B + 1];
-            typename L::Raw raw[B][C];
-            StateV wst[FUSED ? B : 1][C][SV];
-            StateV ast[MODE == MODE_ADAGRAD ? B : 1][C][SV];
+        // Two batches of B rows are in flight: while batch k is added up, the rows of batch k + 1
+        // (and, in the fused modes, the state rows it may need) are on their way and the words of
+        // batch k + 2 are being fetched.  Loads are unconditional so that the hardware counters
+        // can tell exactly which of them a wait is for: past the end of the tile they repeat its
+        // last row, and lanes beyond the row's width read piece 0; neither is used.
+        enum { FB = FUSED ? B : 1, AB = MODE == MODE_ADAGRAD ? B : 1 };
+        const int64_t last = e - 1;
+        size_t piece_off[C];
 #pragma unroll
-            for (int j = 0; j <= B; ++j) w[j] = (r + j < e) ? a.sorted[r + j] : 0ull;
+        for (int c = 0; c < C; ++c) piece_off[c] = (size_t) (live[c] ? piece[c] : 0) * (E * sizeof(T));
+
+        uint64_t wc[B], wn[B], wf[B];
+        typename L::Raw rc[B][C], rn[B][C];
+        StateV wsc[FB][C][SV], wsn[FB][C][SV];
+        StateV asc[AB][C][SV], asn[AB][C][SV];
+
+        auto load_words = [&](int64_t r0, uint64_t (&w)[B]) {
+#pragma unroll
+            for (int j = 0; j < B; ++j) w[j] = a.sorted[r0 + j < e ? r0 + j : last];
+        };
+        auto load_rows = [&](const uint64_t (&w)[B], typename L::Raw (&raw)[B][C]) {
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                const uint32_t payload = (uint32_t) w[j];
+                const uint32_t worker = (a.local_bits >= 32) ? 0u : (payload >> a.local_bits);
+                const char* row = (const char*) s_base[worker] + (size_t) (payload & local_mask) * a.row_bytes;
+#pragma unroll
+                for (int c = 0; c < C; ++c) raw[j][c] = L::load(row + piece_off[c]);
+            }
+        };
+        // The state rows of the batch starting at r0, for the rows that may finish a run lying
+        // wholly inside the tile.  Whether the batch's last row finishes its run depends on a
+        // word that is still in flight: its state row is requested on the chance that it does.
+        auto load_state = [&](int64_t r0, bool st, const uint64_t (&w)[B], StateV (&ws)[FB][C][SV],
+                              StateV (&as)[AB][C][SV]) {
+            if (!FUSED) return;
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                const bool last_of_tile = r0 + j + 1 >= e;
+                const bool may_end = (r0 + j < e) && (last_of_tile || j == B - 1 || key_of(w[j < B - 1 ? j + 1 : j]) != key_of(w[j]));
+                if (may_end && st && (!last_of_tile || next_is_head)) {
+                    const size_t off = (size_t) key_of(w[j]) * a.dim;
+#pragma unroll
+                    for (int c = 0; c < C; ++c)
+                        if (live[c]) {
+#pragma unroll
+                            for (int v = 0; v < SV; ++v) {
+                                ws[FUSED ? j : 0][c][v] = ((const StateV*) (a.table + off + (size_t) piece[c] * E))[v];
+                                if (MODE == MODE_ADAGRAD)
+                                    as[MODE == MODE_ADAGRAD ? j : 0][c][v] = ((const StateV*) (a.accum + off + (size_t) piece[c] * E))[v];
+                            }
+                        }
+                }
+                if (may_end) st = true;
+            }
+        };
+
+        load_words(s, wc);
+        load_words(s + B, wn);
+        load_rows(wc, rc);
+        load_state(s, started, wc, wsc, asc);
+
+        for (int64_t r = s; r < e; r += B) {
             // which rows of the batch finish a run, and is that run wholly inside the tile?
             bool ends[B], whole[B];
-            {
-                bool st = started;
-#pragma unroll
-                for (int j = 0; j < B; ++j) {
-                    const bool last_of_tile = r + j + 1 >= e;
-                    ends[j] = (r + j < e) && (last_of_tile || key_of(w[j + 1]) != key_of(w[j]));
-                    whole[j] = ends[j] && st && (!last_of_tile || next_is_head);
-                    if (ends[j]) st = true;
-                }
-            }
+            bool st = started;
 #pragma unroll
             for (int j = 0; j < B; ++j) {
-                if (r + j < e) {
-                    const uint32_t payload = (uint32_t) w[j];
-                    const uint32_t worker = (a.local_bits >= 32) ? 0u : (payload >> a.local_bits);
-                    const char* row = (const char*) s_base[worker] + (size_t) (payload & local_mask) * a.row_bytes;
-#pragma unroll
-                    for (int c = 0; c < C; ++c)
-                        if (live[c]) raw[j][c] = L::load(row + (size_t) piece[c] * (E * sizeof(T)));
-                    if (FUSED && whole[j]) {
-                        const size_t off = (size_t) key_of(w[j]) * a.dim;
-#pragma unroll
-                        for (int c = 0; c < C; ++c)
-                            if (live[c]) {
-#pragma unroll
-                                for (int v = 0; v < SV; ++v) {
-                                    wst[j][c][v] = ((const StateV*) (a.table + off + (size_t) piece[c] * E))[v];
-                                    if (MODE == MODE_ADAGRAD)
-                                        ast[j][c][v] = ((const StateV*) (a.accum + off + (size_t) piece[c] * E))[v];
-                                }
-                            }
-                    }
-                }
+                const bool last_of_tile = r + j + 1 >= e;
+                const uint64_t after = j < B - 1 ? wc[j < B - 1 ? j + 1 : j] : wn[0];
+                ends[j] = (r + j < e) && (last_of_tile || key_of(after) != key_of(wc[j]));
+                whole[j] = ends[j] && st && (!last_of_tile || next_is_head);
+                if (ends[j]) st = true;
             }
+            load_words(r + 2 * B, wf);
+            load_rows(wn, rn);
+            load_state(r + B, st, wn, wsn, asn);
+
 #pragma unroll
             for (int j = 0; j < B; ++j) {
                 if (r + j < e) {
 #pragma unroll
                     for (int c = 0; c < C; ++c)
-                        if (live[c]) L::add(acc[c], raw[j][c]);
+                        if (live[c]) L::add(acc[c], rc[j][c]);
                     if (ends[j]) {
                         const bool last_of_tile = r + j + 1 >= e;
                         if (whole[j]) {
                             if (!FUSED) {
                                 write_row();
                             } else {
-                                const size_t off = (size_t) key_of(w[j]) * a.dim;
+                                const size_t off = (size_t) key_of(wc[j]) * a.dim;
 #pragma unroll
                                 for (int c = 0; c < C; ++c)
                                     if (live[c]) {
-                                        float* wf = (float*) &wst[j][c][0];
-                                        float* af = (float*) &ast[MODE == MODE_ADAGRAD ? j : 0][c][0];
+                                        float* wf32 = (float*) &wsc[FUSED ? j : 0][c][0];
+                                        float* af32 = (float*) &asc[MODE == MODE_ADAGRAD ? j : 0][c][0];
 #pragma unroll
                                         for (int x = 0; x < E; ++x) {
                                             const float g = (float) ((double) acc[c][x] * a.scale);
-                                            if (MODE == MODE_ADAGRAD) pxu::adagrad(wf[x], af[x], g, a.lr, a.eps);
-                                            else pxu::sgd(wf[x], g, a.lr);
+                                            if (MODE == MODE_ADAGRAD) pxu::adagrad(wf32[x], af32[x], g, a.lr, a.eps);
+                                            else pxu::sgd(wf32[x], g, a.lr);
                                         }
 #pragma unroll
                                         for (int v = 0; v < SV; ++v) {
-                                            ((StateV*) (a.table + off + (size_t) piece[c] * E))[v] = wst[j][c][v];
+                                            ((StateV*) (a.table + off + (size_t) piece[c] * E))[v] = wsc[FUSED ? j : 0][c][v];
                                             if (MODE == MODE_ADAGRAD)
-                                                ((StateV*) (a.accum + off + (size_t) piece[c] * E))[v] = ast[j][c][v];
+                                                ((StateV*) (a.accum + off + (size_t) piece[c] * E))[v] = asc[MODE == MODE_ADAGRAD ? j : 0][c][v];
                                         }
                                     }
                             }
@@ -627,6 +665,24 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
                         }
                     }
                 }
+            }
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                wc[j] = wn[j];
+                wn[j] = wf[j];
+#pragma unroll
+                for (int c = 0; c < C; ++c) rc[j][c] = rn[j][c];
+            }
+            if (FUSED) {
+#pragma unroll
+                for (int j = 0; j < FB; ++j)
+#pragma unroll
+                    for (int c = 0; c < C; ++c)
+#pragma unroll
+                        for (int v = 0; v < SV; ++v) {
+                            wsc[j][c][v] = wsn[j][c][v];
+                            if (MODE == MODE_ADAGRAD) asc[MODE == MODE_ADAGRAD ? j : 0][c][v] = asn[MODE == MODE_ADAGRAD ? j : 0][c][v];
+                        }
             }
         }
     }
@@ -814,7 +870,7 @@ int bits_for(uint64_t max_value) {   // bits needed to write max_value
 // Rows in flight per lane group.  The fused modes also hold the table (and accumulator) pieces of
 // every row of a batch that may finish a run, so their batches shrink as rows get wider.
 constexpr int batch_rows(int mode, int c, int state_vectors) {
-    if (mode == MODE_ROWS) return c <= 2 ? PX_SEG_ROWS : PX_SEG_ROWS_WIDE;
+    if (mode == MODE_ROWS) return c == 1 ? PX_SEG_ROWS : c == 2 ? PX_SEG_ROWS_2 : PX_SEG_ROWS_WIDE;
     const int per_row = c * state_vectors * (mode == MODE_ADAGRAD ? 2 : 1);
     return per_row >= 8 ? 1 : 8 / per_row;
 }
