@@ -85,7 +85,8 @@ inline int64_t max_partial_stride(int64_t dim) {
     return best;
 }
 
-// Per tile: x = first row, y = flags, z = run index of the first row.
+// Per tile: x = first row, y = flags, z = run index of the first row, w = first head at or after the
+// first row inside the tile's window (0xffffffff: none).
 enum : uint32_t {
     TILE_STARTS_AT_HEAD = 1u,   // the first row is a run head
     TILE_HAS_HEAD = 2u          // some row of the tile's window is a run head
@@ -228,9 +229,15 @@ __global__ __launch_bounds__(256) void k_heads_count(const uint64_t* __restrict_
 
 // Ranks the heads: distinct ids, run starts, U; and for every window of tile_rows rows the tile
 // that starts there: its first row (the first head in the leading part of the window, else the
-// window's own first row), the run that row belongs to, and whether the window holds any head.
+// window's own first row), the run that row belongs to, and the first head at or after that row
+// inside the window.  It also writes every row's reference for the segmented sum: the address of
+// its value row, with bit 0 set when the row is the last of its run (value rows are at least
+// 2-byte aligned, so the bit is free).
 __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__ sorted, int64_t m,
                                                     const uint32_t* __restrict__ hcount, int tile_rows,
+                                                    const uint64_t* __restrict__ words, int n_workers,
+                                                    int local_bits, int64_t row_bytes,
+                                                    uint64_t* __restrict__ rowref,
                                                     int64_t* __restrict__ out_ids,
                                                     uint32_t* __restrict__ run_start,
                                                     uint4* __restrict__ tile_info,
@@ -238,12 +245,14 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
                                                     const uint32_t* __restrict__ flags) {
     __shared__ uint32_t s_wave[4];
     __shared__ uint32_t s_first[PX_SORT_TILE / 32];        // first aligning head of each window of this block
-    __shared__ uint32_t s_any[PX_SORT_TILE / 32];          // does the window hold a head at all
+    __shared__ uint32_t s_head[PX_SORT_TILE / 32];         // first head of the window, 0xffffffff if it has none
+    __shared__ uint64_t s_vbase[PX_MAX_SOURCES];           // the workers' value buffers
     const int tid = threadIdx.x;
     if (tid < PX_SORT_TILE / 32) {
         s_first[tid] = 0xffffffffu;
-        s_any[tid] = 0u;
+        s_head[tid] = 0xffffffffu;
     }
+    for (int i = tid; i < n_workers; i += 256) s_vbase[i] = words[n_workers + i];
     // heads in all blocks before this one
     uint32_t part = 0;
     for (int b = tid; b < (int) blockIdx.x; b += 256) part += hcount[b];
@@ -254,45 +263,47 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
     const int64_t base = (int64_t) block_base + (int64_t) tid * PX_SORT_ITEMS;
     // A head at a window's first row always starts the tile (align_rows >= 1), so every tile gets a start.
     const uint32_t align_rows = (uint32_t) tile_rows / PX_ALIGN_DIV > 0u ? (uint32_t) tile_rows / PX_ALIGN_DIV : 1u;
-    uint32_t keys[PX_SORT_ITEMS];
+    uint64_t w[PX_SORT_ITEMS];
     uint32_t flag[PX_SORT_ITEMS];
     uint32_t prev = 0;
     if (base > 0 && base - 1 < m) prev = key_of(sorted[base - 1]);
     uint32_t cnt = 0;
 #pragma unroll
+    for (int j = 0; j < PX_SORT_ITEMS; ++j) w[j] = (base + j < m) ? sorted[base + j] : 0ull;
+#pragma unroll
     for (int j = 0; j < PX_SORT_ITEMS; ++j) {
         const int64_t i = base + j;
-        keys[j] = 0;
         flag[j] = 0;
         if (i < m) {
-            keys[j] = key_of(sorted[i]);
-            flag[j] = (i == 0 || keys[j] != prev) ? 1u : 0u;
-            prev = keys[j];
+            flag[j] = (i == 0 || key_of(w[j]) != prev) ? 1u : 0u;
+            prev = key_of(w[j]);
             if (flag[j]) {
-                const uint32_t w = ((uint32_t) i - block_base) / (uint32_t) tile_rows;
-                s_any[w] = 1u;
-                if ((uint32_t) i % (uint32_t) tile_rows < align_rows) atomicMin(&s_first[w], (uint32_t) i);
+                const uint32_t win = ((uint32_t) i - block_base) / (uint32_t) tile_rows;
+                atomicMin(&s_head[win], (uint32_t) i);
+                if ((uint32_t) i % (uint32_t) tile_rows < align_rows) atomicMin(&s_first[win], (uint32_t) i);
             }
         }
         cnt += flag[j];
     }
     uint32_t block_total;
     uint32_t rank = before + pxr::block_exclusive_scan_256(cnt, s_wave, &block_total);   // syncs
+    const uint32_t local_mask = (local_bits >= 32) ? 0xffffffffu : ((1u << local_bits) - 1u);
 #pragma unroll
     for (int j = 0; j < PX_SORT_ITEMS; ++j) {
         const int64_t i = base + j;
         if (i < m) {
-            const uint32_t w = ((uint32_t) i - block_base) / (uint32_t) tile_rows;
+            const uint32_t win = ((uint32_t) i - block_base) / (uint32_t) tile_rows;
             const uint32_t t = (uint32_t) i / (uint32_t) tile_rows;
             if (flag[j]) {
-                out_ids[rank] = (int64_t) keys[j];
+                out_ids[rank] = (int64_t) key_of(w[j]);
                 run_start[rank] = (uint32_t) i;
-                if (s_first[w] == (uint32_t) i)
-                    tile_info[t] = make_uint4((uint32_t) i, TILE_STARTS_AT_HEAD | TILE_HAS_HEAD, rank, 0u);
+                if (s_first[win] == (uint32_t) i)
+                    tile_info[t] = make_uint4((uint32_t) i, TILE_STARTS_AT_HEAD | TILE_HAS_HEAD, rank, (uint32_t) i);
                 ++rank;
-            } else if ((uint32_t) i % (uint32_t) tile_rows == 0u && s_first[w] == 0xffffffffu) {
+            } else if ((uint32_t) i % (uint32_t) tile_rows == 0u && s_first[win] == 0xffffffffu) {
                 // no head to move to: the tile keeps its border and continues the run row i belongs to
-                tile_info[t] = make_uint4((uint32_t) i, s_any[w] ? TILE_HAS_HEAD : 0u, rank - 1u, 0u);
+                tile_info[t] = make_uint4((uint32_t) i, s_head[win] != 0xffffffffu ? TILE_HAS_HEAD : 0u, rank - 1u,
+                                          s_head[win]);
             }
         }
     }
@@ -300,6 +311,18 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
         const uint32_t u = before + block_total;
         run_start[u] = (uint32_t) m;
         out_num_unique[0] = (flags[0] & PXF_BAD_ID) ? 0 : (int64_t) u;
+    }
+    // row references, consecutive lanes on consecutive rows so that the stores coalesce
+#pragma unroll
+    for (int j = 0; j < PX_SORT_ITEMS; ++j) {
+        const int64_t i = (int64_t) block_base + j * 256 + tid;
+        if (i < m) {
+            const uint64_t wi = sorted[i];
+            const bool tail = i + 1 >= m || key_of(sorted[i + 1]) != key_of(wi);
+            const uint32_t payload = (uint32_t) wi;
+            const uint32_t worker = (local_bits >= 32) ? 0u : (payload >> local_bits);
+            rowref[i] = (s_vbase[worker] + (uint64_t) (payload & local_mask) * (uint64_t) row_bytes) | (tail ? 1ull : 0ull);
+        }
     }
 }
 
@@ -324,15 +347,20 @@ __global__ void k_write_zero_count(int64_t* out_num_unique) {
 typedef PX_SEG_ACC seg_acc_t;
 
 typedef uint32_t seg_v4u __attribute__((ext_vector_type(4)));
-// Value rows are read exactly once.
+// Value rows are read exactly once, through addresses that were carried as integers: the loads
+// name the global address space so that they are global (not flat) instructions.
+#define PX_GLOBAL __attribute__((address_space(1)))
 __device__ __forceinline__ uint4 seg_load16(const char* p) {
+    const PX_GLOBAL seg_v4u* g = (const PX_GLOBAL seg_v4u*) (uintptr_t) p;
 #ifdef PX_SEG_TEMPORAL
-    return *(const uint4*) p;
+    seg_v4u v = *g;
 #else
-    seg_v4u v = __builtin_nontemporal_load((const seg_v4u*) p);     // stream past the caches
-    return make_uint4(v.x, v.y, v.z, v.w);
+    seg_v4u v = __builtin_nontemporal_load(g);      // stream past the caches
 #endif
+    return make_uint4(v.x, v.y, v.z, v.w);
 }
+__device__ __forceinline__ float seg_load_f32(const char* p) { return *(const PX_GLOBAL float*) (uintptr_t) p; }
+__device__ __forceinline__ uint16_t seg_load_u16(const char* p) { return *(const PX_GLOBAL uint16_t*) (uintptr_t) p; }
 
 typedef float seg_v4f __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void seg_store16(float* p, float4 v) {
@@ -360,7 +388,7 @@ template <> struct RowLoad<float, true> {
 template <> struct RowLoad<float, false> {
     typedef float Raw;
     enum { E = 1 };
-    static __device__ __forceinline__ Raw load(const char* p) { return *(const float*) p; }
+    static __device__ __forceinline__ Raw load(const char* p) { return seg_load_f32(p); }
     static __device__ __forceinline__ void add(seg_acc_t* acc, const Raw& r) { acc[0] += (seg_acc_t) r; }
 };
 // bfloat16 is the upper half of a float32: widening is a shift.
@@ -382,7 +410,7 @@ template <> struct RowLoad<uint16_t, true> {
 template <> struct RowLoad<uint16_t, false> {
     typedef uint16_t Raw;
     enum { E = 1 };
-    static __device__ __forceinline__ Raw load(const char* p) { return *(const uint16_t*) p; }
+    static __device__ __forceinline__ Raw load(const char* p) { return seg_load_u16(p); }
     static __device__ __forceinline__ void add(seg_acc_t* acc, const Raw& r) {
         acc[0] += (seg_acc_t) __uint_as_float((uint32_t) r << 16);
     }
@@ -391,8 +419,8 @@ template <> struct RowLoad<uint16_t, false> {
 enum { MODE_ROWS = 0, MODE_SGD = 1, MODE_ADAGRAD = 2 };   // what becomes of a finished run
 
 struct SegsumArgs {
-    const uint64_t* sorted;       // packed words in id order
-    const uint64_t* words;        // context table: [idx pointers | value pointers | prefix]
+    const uint64_t* rowref;       // per row in id order: address of its value row | 1 if it ends its run
+    const uint64_t* sorted;       // packed words in id order (the fused modes read the ids)
     const uint4* tile_info;
     const uint32_t* run_start;
     double* pfirst;
@@ -407,10 +435,7 @@ struct SegsumArgs {
     int64_t m;
     int64_t n_tiles;
     int64_t dim;                  // elements per row
-    int64_t row_bytes;            // bytes per input row
     int64_t pstride;              // doubles per partial row
-    int n_workers;
-    int local_bits;
     int tile_rows;
     int pieces;                   // row pieces (E elements each) per row
     float scale;
@@ -419,43 +444,49 @@ struct SegsumArgs {
 };
 
 // G lanes walk one tile; lane l owns pieces slab*G*C + c*G + l, c < C, E elements each.
-// B rows are in flight at once.  A partial row is stored lane-interleaved so that every store
-// instruction writes one contiguous block: pair p of piece c sits at ((slab*C + c)*(E/2) + p)*G + l.
+// A partial row is stored lane-interleaved so that every store instruction writes one contiguous
+// block: pair p of piece c sits at ((slab*C + c)*(E/2) + p)*G + l.
 //
-// A block holds 256/G consecutive tiles.  When all of them lie strictly inside one run (none of
-// their windows holds a head and the run goes on into the next block) their partial rows are
-// added in LDS, in tile order, and stored once, as the partial row of the block's first tile: a
-// long run then leaves one partial row per block instead of one per tile.
+// A tile is walked in two stretches.  Rows before its first head continue the run that entered
+// from the tile before: they are only added up, and the sum is left as the tile's "first" partial
+// row.  From the first head on, every row whose reference carries the tail bit finishes a run that
+// lies wholly inside the tile: MODE_ROWS writes its sum as a float row, the fused modes apply the
+// optimizer to the variable's row instead (Parallax Sec. 4.3 puts the aggregation next to the
+// variable so the aggregate never travels).  What is left when the tile ends belongs to a run
+// that goes on into the next tile (the "last" partial row).
 //
-// MODE_ROWS writes a finished run's sum as a float row.  The fused modes apply the optimizer to
-// the variable's row instead (Parallax Sec. 4.3 puts the aggregation next to the variable so the
-// aggregate never travels): the words of the next B rows are known before their value rows are
-// requested, so the table (and accumulator) rows of the runs that finish among them are
-// requested in the same breath and have arrived when the sum is complete.
+// Each stretch keeps two batches of B rows in flight: while batch k is added up, the rows of
+// batch k + 1 (and, in the fused modes, the table and accumulator rows of its tails) are on
+// their way and the references of batch k + 2 are being fetched.  Loads are unconditional, so the
+// hardware counters tell exactly which of them a wait is for: past the end of the stretch they
+// repeat its last row, and lanes beyond the row's width read piece 0; neither is used.
+//
+// A block holds 256/G consecutive tiles.  When all of them lie strictly inside one run (no head
+// inside, and the run goes on into the next block) their sums are added in LDS, in tile order,
+// and stored once, as the partial row of the block's first tile: a long run then leaves one
+// partial row per block instead of one per tile.
 template <typename T, bool VEC, int G, int C, int B, int MODE>
 __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
     typedef RowLoad<T, VEC> L;
+    typedef typename L::Raw Raw;
     enum { E = L::E, TPB = 256 / G, MERGE = (C * E <= 16) ? 1 : 0, FUSED = MODE != MODE_ROWS ? 1 : 0,
-           SV = VEC ? E / 4 : 1 };                                // state vectors (float4 or float) per piece
+           SV = VEC ? E / 4 : 1,                                  // state vectors (float4 or float) per piece
+           FB = FUSED ? B : 1, AB = MODE == MODE_ADAGRAD ? B : 1 };
     typedef typename std::conditional<VEC, float4, float>::type StateV;
-    __shared__ uint64_t s_base[PX_MAX_SOURCES];
     __shared__ double s_part[MERGE ? TPB * G * C * E : 1];
-    for (int i = threadIdx.x; i < a.n_workers; i += 256) s_base[i] = a.words[a.n_workers + i];
-    __syncthreads();
     if (FUSED && (a.flags[0] & PXF_BAD_ID)) return;               // uniform: a bad id was seen, touch nothing
 
     const int gl = threadIdx.x % G;
     const int gj = threadIdx.x / G;                               // tile inside the block
     const int64_t tile = (int64_t) blockIdx.x * TPB + gj;
     const bool active = tile < a.n_tiles;
-    int64_t s = 0, e = 0;
-    bool started = false, next_is_head = true, pure = false;
+    int64_t s = 0, e = 0, h = 0;
+    bool started = false, next_is_head = true;
     uint32_t u = 0;
     if (active) {
         const uint4 ti = a.tile_info[tile];
         s = (int64_t) ti.x;
         started = (ti.y & TILE_STARTS_AT_HEAD) != 0u;
-        pure = (ti.y & TILE_HAS_HEAD) == 0u;
         u = ti.z;
         e = a.m;
         if (tile + 1 < a.n_tiles) {
@@ -463,32 +494,30 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
             e = (int64_t) tn.x;
             next_is_head = (tn.y & TILE_STARTS_AT_HEAD) != 0u;
         }
+        h = (int64_t) ti.w < e ? (int64_t) ti.w : e;              // first head inside the tile, else its end
     }
-    // the last tile of the block also vouches for the run going on into the next block
-    const bool inside = active && pure && (gj < TPB - 1 || !next_is_head);
+    // no head inside; the last tile of the block also vouches for the run going on into the next block
+    const bool inside = active && h >= e && (gj < TPB - 1 || !next_is_head);
     const bool merged = MERGE ? (__syncthreads_and(inside ? 1 : 0) != 0) : false;
 
     int piece[C];
     bool live[C];
+    size_t piece_off[C];
 #pragma unroll
     for (int c = 0; c < C; ++c) {
         piece[c] = (int) blockIdx.y * (G * C) + c * G + gl;
         live[c] = piece[c] < a.pieces;
+        piece_off[c] = (size_t) (live[c] ? piece[c] : 0) * (E * sizeof(T));
     }
-    const uint32_t local_mask = (a.local_bits >= 32) ? 0xffffffffu : ((1u << a.local_bits) - 1u);
 
     seg_acc_t acc[C][E];
-#pragma unroll
-    for (int c = 0; c < C; ++c)
-#pragma unroll
-        for (int x = 0; x < E; ++x) acc[c][x] = (seg_acc_t) 0;
-
     auto clear = [&]() {
 #pragma unroll
         for (int c = 0; c < C; ++c)
 #pragma unroll
             for (int x = 0; x < E; ++x) acc[c][x] = (seg_acc_t) 0;
     };
+    clear();
 
     auto store_partial = [&](double* dst) {
 #pragma unroll
@@ -505,82 +534,50 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
         }
     };
 
-    // a run that started in this tile goes on into the next one
-    auto leave_open = [&]() {
-        store_partial(a.plast + (size_t) tile * a.pstride);
-        if (gl == 0 && blockIdx.y == 0) {
-            // record where the run ends
-            const uint32_t last_row = a.run_start[u + 1] - 1u;
-            uint32_t last_tile = last_row / (uint32_t) a.tile_rows;
-            if (a.tile_info[last_tile].x > last_row) --last_tile;
-            const bool is_long = last_tile - (uint32_t) tile > (uint32_t) SPAN_LONG_TILES;
-            const uint32_t slot = atomicAdd(a.counters + (is_long ? 0 : 1), 1u);
-            (is_long ? a.span_long : a.span_short)[slot] = make_uint4(u, (uint32_t) tile, last_tile, 0u);
-        }
-    };
-
-    // a run that lies wholly inside this tile: MODE_ROWS
-    auto write_row = [&]() {
-        float* dst = a.out_rows + (size_t) u * a.dim;
-#pragma unroll
-        for (int c = 0; c < C; ++c)
-            if (live[c]) {
-                if (VEC) {
-#pragma unroll
-                    for (int x = 0; x < E; x += 4) {
-                        float4 o = make_float4((float) ((double) acc[c][x] * a.scale), (float) ((double) acc[c][x + 1] * a.scale),
-                                               (float) ((double) acc[c][x + 2] * a.scale), (float) ((double) acc[c][x + 3] * a.scale));
-                        seg_store16(dst + (size_t) piece[c] * E + x, o);
-                    }
-                } else {
-                    dst[piece[c]] = (float) ((double) acc[c][0] * a.scale);
-                }
-            }
-    };
-
-    if (active) {
-        // Two batches of B rows are in flight: while batch k is added up, the rows of batch k + 1
-        // (and, in the fused modes, the state rows it may need) are on their way and the words of
-        // batch k + 2 are being fetched.  Loads are unconditional so that the hardware counters
-        // can tell exactly which of them a wait is for: past the end of the tile they repeat its
-        // last row, and lanes beyond the row's width read piece 0; neither is used.
-        enum { FB = FUSED ? B : 1, AB = MODE == MODE_ADAGRAD ? B : 1 };
-        const int64_t last = e - 1;
-        size_t piece_off[C];
-#pragma unroll
-        for (int c = 0; c < C; ++c) piece_off[c] = (size_t) (live[c] ? piece[c] : 0) * (E * sizeof(T));
-
-        uint64_t wc[B], wn[B], wf[B];
-        typename L::Raw rc[B][C], rn[B][C];
+    // Rows [from, to), from < to, are added to acc.  With TAILS, a row whose reference carries
+    // the tail bit finishes run u: its sum is written (or applied) and acc starts again.
+    auto walk = [&](int64_t from, int64_t to, auto tails_tag) {
+        constexpr bool TAILS = decltype(tails_tag)::value;
+        constexpr bool STATE = TAILS && FUSED;
+        const int64_t lastrow = to - 1;
+        uint64_t wn[B], wf[B];                                    // references of the next batch and the one after
+        uint32_t kc[FB], kn[FB], kf[FB];                          // fused modes: the rows' ids
+        Raw rc[B][C], rn[B][C];
+        uint32_t tc = 0, tn = 0;                                  // tail bits of the current and the next batch
         StateV wsc[FB][C][SV], wsn[FB][C][SV];
         StateV asc[AB][C][SV], asn[AB][C][SV];
+        float* dst = a.out_rows + (size_t) u * a.dim + (size_t) piece[0] * E;   // MODE_ROWS: lane's place in row u
 
-        auto load_words = [&](int64_t r0, uint64_t (&w)[B]) {
-#pragma unroll
-            for (int j = 0; j < B; ++j) w[j] = a.sorted[r0 + j < e ? r0 + j : last];
-        };
-        auto load_rows = [&](const uint64_t (&w)[B], typename L::Raw (&raw)[B][C]) {
+        auto load_refs = [&](int64_t r0, uint64_t (&w)[B], uint32_t (&k)[FB]) {
 #pragma unroll
             for (int j = 0; j < B; ++j) {
-                const uint32_t payload = (uint32_t) w[j];
-                const uint32_t worker = (a.local_bits >= 32) ? 0u : (payload >> a.local_bits);
-                const char* row = (const char*) s_base[worker] + (size_t) (payload & local_mask) * a.row_bytes;
+                const int64_t i = r0 + j < to ? r0 + j : lastrow;
+                w[j] = a.rowref[i];
+                if (STATE) k[FUSED ? j : 0] = ((const uint32_t*) a.sorted)[2 * i + 1];
+            }
+        };
+        auto load_rows = [&](const uint64_t (&w)[B], Raw (&raw)[B][C]) {
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                const char* row = (const char*) (w[j] & ~1ull);
 #pragma unroll
                 for (int c = 0; c < C; ++c) raw[j][c] = L::load(row + piece_off[c]);
             }
         };
-        // The state rows of the batch starting at r0, for the rows that may finish a run lying
-        // wholly inside the tile.  Whether the batch's last row finishes its run depends on a
-        // word that is still in flight: its state row is requested on the chance that it does.
-        auto load_state = [&](int64_t r0, bool st, const uint64_t (&w)[B], StateV (&ws)[FB][C][SV],
-                              StateV (&as)[AB][C][SV]) {
-            if (!FUSED) return;
+        auto tails_of = [&](int64_t r0, const uint64_t (&w)[B]) -> uint32_t {
+            if (!TAILS) return 0u;
+            uint32_t t = 0;
 #pragma unroll
-            for (int j = 0; j < B; ++j) {
-                const bool last_of_tile = r0 + j + 1 >= e;
-                const bool may_end = (r0 + j < e) && (last_of_tile || j == B - 1 || key_of(w[j < B - 1 ? j + 1 : j]) != key_of(w[j]));
-                if (may_end && st && (!last_of_tile || next_is_head)) {
-                    const size_t off = (size_t) key_of(w[j]) * a.dim;
+            for (int j = 0; j < B; ++j) t |= ((uint32_t) w[j] & 1u) << j;
+            const int64_t left = to - r0;
+            return left >= B ? t : (left > 0 ? t & ((1u << (int) left) - 1u) : 0u);
+        };
+        auto load_state = [&](uint32_t t, const uint32_t (&k)[FB], StateV (&ws)[FB][C][SV], StateV (&as)[AB][C][SV]) {
+            if (!STATE) return;
+#pragma unroll
+            for (int j = 0; j < B; ++j)
+                if ((t >> j) & 1u) {
+                    const size_t off = (size_t) k[FUSED ? j : 0] * a.dim;
 #pragma unroll
                     for (int c = 0; c < C; ++c)
                         if (live[c]) {
@@ -592,90 +589,93 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
                             }
                         }
                 }
-                if (may_end) st = true;
+        };
+        // row j of the current batch is the last of run u
+        auto finish = [&](int j) {
+            if (!FUSED) {
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    if (live[c]) {
+                        if (VEC) {
+#pragma unroll
+                            for (int x = 0; x < E; x += 4) {
+                                float4 o = make_float4((float) ((double) acc[c][x] * a.scale), (float) ((double) acc[c][x + 1] * a.scale),
+                                                       (float) ((double) acc[c][x + 2] * a.scale), (float) ((double) acc[c][x + 3] * a.scale));
+                                seg_store16(dst + (size_t) c * (G * E) + x, o);
+                            }
+                        } else {
+                            dst[(size_t) c * G] = (float) ((double) acc[c][0] * a.scale);
+                        }
+                    }
+                dst += a.dim;
+            } else {
+                const size_t off = (size_t) kc[FUSED ? j : 0] * a.dim;
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    if (live[c]) {
+                        float* wf32 = (float*) &wsc[FUSED ? j : 0][c][0];
+                        float* af32 = (float*) &asc[MODE == MODE_ADAGRAD ? j : 0][c][0];
+#pragma unroll
+                        for (int x = 0; x < E; ++x) {
+                            const float g = (float) ((double) acc[c][x] * a.scale);
+                            if (MODE == MODE_ADAGRAD) pxu::adagrad(wf32[x], af32[x], g, a.lr, a.eps);
+                            else pxu::sgd(wf32[x], g, a.lr);
+                        }
+#pragma unroll
+                        for (int v = 0; v < SV; ++v) {
+                            ((StateV*) (a.table + off + (size_t) piece[c] * E))[v] = wsc[FUSED ? j : 0][c][v];
+                            if (MODE == MODE_ADAGRAD)
+                                ((StateV*) (a.accum + off + (size_t) piece[c] * E))[v] = asc[MODE == MODE_ADAGRAD ? j : 0][c][v];
+                        }
+                    }
             }
+            ++u;
+            clear();
         };
 
-        load_words(s, wc);
-        load_words(s + B, wn);
-        load_rows(wc, rc);
-        load_state(s, started, wc, wsc, asc);
-
-        for (int64_t r = s; r < e; r += B) {
-            // which rows of the batch finish a run, and is that run wholly inside the tile?
-            bool ends[B], whole[B];
-            bool st = started;
-#pragma unroll
-            for (int j = 0; j < B; ++j) {
-                const bool last_of_tile = r + j + 1 >= e;
-                const uint64_t after = j < B - 1 ? wc[j < B - 1 ? j + 1 : j] : wn[0];
-                ends[j] = (r + j < e) && (last_of_tile || key_of(after) != key_of(wc[j]));
-                whole[j] = ends[j] && st && (!last_of_tile || next_is_head);
-                if (ends[j]) st = true;
-            }
-            load_words(r + 2 * B, wf);
+        {
+            uint64_t w0[B];
+            load_refs(from, w0, kc);
+            load_refs(from + B, wn, kn);
+            load_rows(w0, rc);
+            tc = tails_of(from, w0);
+            load_state(tc, kc, wsc, asc);
+        }
+        for (int64_t r = from; r < to; r += B) {
             load_rows(wn, rn);
-            load_state(r + B, st, wn, wsn, asn);
-
+            tn = tails_of(r + B, wn);
+            load_state(tn, kn, wsn, asn);
+            load_refs(r + 2 * B, wf, kf);
+            if (r + B <= to) {
 #pragma unroll
-            for (int j = 0; j < B; ++j) {
-                if (r + j < e) {
+                for (int j = 0; j < B; ++j) {
 #pragma unroll
                     for (int c = 0; c < C; ++c)
                         if (live[c]) L::add(acc[c], rc[j][c]);
-                    if (ends[j]) {
-                        const bool last_of_tile = r + j + 1 >= e;
-                        if (whole[j]) {
-                            if (!FUSED) {
-                                write_row();
-                            } else {
-                                const size_t off = (size_t) key_of(wc[j]) * a.dim;
-#pragma unroll
-                                for (int c = 0; c < C; ++c)
-                                    if (live[c]) {
-                                        float* wf32 = (float*) &wsc[FUSED ? j : 0][c][0];
-                                        float* af32 = (float*) &asc[MODE == MODE_ADAGRAD ? j : 0][c][0];
-#pragma unroll
-                                        for (int x = 0; x < E; ++x) {
-                                            const float g = (float) ((double) acc[c][x] * a.scale);
-                                            if (MODE == MODE_ADAGRAD) pxu::adagrad(wf32[x], af32[x], g, a.lr, a.eps);
-                                            else pxu::sgd(wf32[x], g, a.lr);
-                                        }
-#pragma unroll
-                                        for (int v = 0; v < SV; ++v) {
-                                            ((StateV*) (a.table + off + (size_t) piece[c] * E))[v] = wsc[FUSED ? j : 0][c][v];
-                                            if (MODE == MODE_ADAGRAD)
-                                                ((StateV*) (a.accum + off + (size_t) piece[c] * E))[v] = asc[MODE == MODE_ADAGRAD ? j : 0][c][v];
-                                        }
-                                    }
-                            }
-                            clear();
-                        } else if (last_of_tile && merged) {
-                            // keep the sum: the block adds its tiles up below
-                        } else if (started) {
-                            leave_open();                       // only the tile's last run can stay open
-                            clear();
-                        } else {
-                            store_partial(a.pfirst + (size_t) tile * a.pstride);     // entered from the tile before
-                            clear();
-                        }
-                        if (!last_of_tile) {
-                            ++u;
-                            started = true;
-                        }
-                    }
+                    if (TAILS && ((tc >> j) & 1u)) finish(j);
                 }
+            } else {
+#pragma unroll
+                for (int j = 0; j < B; ++j)
+                    if (r + j < to) {
+#pragma unroll
+                        for (int c = 0; c < C; ++c)
+                            if (live[c]) L::add(acc[c], rc[j][c]);
+                        if (TAILS && ((tc >> j) & 1u)) finish(j);
+                    }
             }
+            tc = tn;
 #pragma unroll
             for (int j = 0; j < B; ++j) {
-                wc[j] = wn[j];
                 wn[j] = wf[j];
 #pragma unroll
                 for (int c = 0; c < C; ++c) rc[j][c] = rn[j][c];
             }
-            if (FUSED) {
+            if (STATE) {
 #pragma unroll
-                for (int j = 0; j < FB; ++j)
+                for (int j = 0; j < FB; ++j) {
+                    kc[j] = kn[j];
+                    kn[j] = kf[j];
 #pragma unroll
                     for (int c = 0; c < C; ++c)
 #pragma unroll
@@ -683,6 +683,37 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
                             wsc[j][c][v] = wsn[j][c][v];
                             if (MODE == MODE_ADAGRAD) asc[MODE == MODE_ADAGRAD ? j : 0][c][v] = asn[MODE == MODE_ADAGRAD ? j : 0][c][v];
                         }
+                }
+            }
+        }
+    };
+
+    if (active) {
+        if (!started) {
+            // the run that entered from the tile before
+            walk(s, h, std::false_type());
+            if (h < e) {
+                store_partial(a.pfirst + (size_t) tile * a.pstride);
+                clear();
+                ++u;
+            } else if (!merged) {
+                store_partial(a.pfirst + (size_t) tile * a.pstride);
+            }
+        }
+        if (h < e) {
+            walk(h, e, std::true_type());
+            if (!next_is_head) {
+                // the tile's last run goes on into the next tile
+                store_partial(a.plast + (size_t) tile * a.pstride);
+                if (gl == 0 && blockIdx.y == 0) {
+                    // record where the run ends
+                    const uint32_t last_row = a.run_start[u + 1] - 1u;
+                    uint32_t last_tile = last_row / (uint32_t) a.tile_rows;
+                    if (a.tile_info[last_tile].x > last_row) --last_tile;
+                    const bool is_long = last_tile - (uint32_t) tile > (uint32_t) SPAN_LONG_TILES;
+                    const uint32_t slot = atomicAdd(a.counters + (is_long ? 0 : 1), 1u);
+                    (is_long ? a.span_long : a.span_short)[slot] = make_uint4(u, (uint32_t) tile, last_tile, 0u);
+                }
             }
         }
     }
@@ -1003,13 +1034,15 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
     const int64_t n_tiles = (m + tile_rows - 1) / tile_rows;
     const int n_hblocks = (int) ((m + PX_SORT_TILE - 1) / PX_SORT_TILE);
     k_heads_count<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount);
-    k_heads_emit<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount, tile_rows, out_ids, sc.run_start,
-                                                sc.tile_info, out_num_unique, ctx->d_flags);
+    uint64_t* rowref = dst;               // the sort's other buffer is free now
+    k_heads_emit<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount, tile_rows, ctx->d_words, n_workers, local_bits,
+                                                dim * (int64_t) es, rowref, out_ids, sc.run_start, sc.tile_info,
+                                                out_num_unique, ctx->d_flags);
 
     const RowShape sh = row_shape(dim, (int) es, vec);
     SegsumArgs a;
+    a.rowref = rowref;
     a.sorted = sorted;
-    a.words = ctx->d_words;
     a.tile_info = sc.tile_info;
     a.run_start = sc.run_start;
     a.pfirst = sc.pfirst;
@@ -1021,10 +1054,7 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
     a.m = m;
     a.n_tiles = n_tiles;
     a.dim = dim;
-    a.row_bytes = dim * (int64_t) es;
     a.pstride = sh.pstride;
-    a.n_workers = n_workers;
-    a.local_bits = local_bits;
     a.tile_rows = tile_rows;
     a.pieces = sh.pieces;
     a.scale = scale;
