@@ -852,7 +852,16 @@ __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc += v[j];
             }
-            for (; q < pl.parts; q += FIX_SPLITS) acc += pl.row(q, a.pfirst, a.plast, a.pstride)[pe];
+            {
+                // at most seven parts are left for this wave: request them together, add them in order
+                double v[7];
+#pragma unroll
+                for (int j = 0; j < 7; ++j)
+                    v[j] = q + j * FIX_SPLITS < pl.parts ? pl.row(q + j * FIX_SPLITS, a.pfirst, a.plast, a.pstride)[pe] : 0.0;
+#pragma unroll
+                for (int j = 0; j < 7; ++j)
+                    if (q + j * FIX_SPLITS < pl.parts) acc += v[j];
+            }
         }
         s_red[split][lane] = acc;
         __syncthreads();
@@ -864,20 +873,38 @@ __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
         }
         __syncthreads();
     }
-    for (uint32_t i = blockIdx.x * FIX_SPLITS + split; i < n_short; i += gridDim.x * FIX_SPLITS) {
+    // the short spans are dealt out from the far end of the grid: the workgroups that had a long
+    // run to add up get theirs last
+    for (uint32_t i = (gridDim.x - 1u - blockIdx.x) * FIX_SPLITS + split; i < n_short; i += gridDim.x * FIX_SPLITS) {
         const uint4 rec = a.span_short[i];
         const PartList pl(rec.y, rec.z, (uint32_t) a.tiles_per_block);
         if (live) {
             double acc = 0.0;
             uint32_t q = 0;
-            for (; q + 3 < pl.parts; q += 4) {
+            for (; q + 7 < pl.parts; q += 8) {
+                double v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = pl.row(q + j, a.pfirst, a.plast, a.pstride)[pe];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc += v[j];
+            }
+            if (q + 3 < pl.parts) {
                 double v[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) v[j] = pl.row(q + j, a.pfirst, a.plast, a.pstride)[pe];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) acc += v[j];
+                q += 4;
             }
-            for (; q < pl.parts; ++q) acc += pl.row(q, a.pfirst, a.plast, a.pstride)[pe];
+            {
+                // at most three parts are left: request them together, add them in order
+                double v[3];
+#pragma unroll
+                for (int j = 0; j < 3; ++j) v[j] = q + j < pl.parts ? pl.row(q + j, a.pfirst, a.plast, a.pstride)[pe] : 0.0;
+#pragma unroll
+                for (int j = 0; j < 3; ++j)
+                    if (q + j < pl.parts) acc += v[j];
+            }
             fixup_finish(a, rec.x, col, acc);
         }
     }
@@ -1022,8 +1049,9 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
     for (int p = 0; p < passes; ++p) {
         SortWords pol{src, dst, m, 8 * p};
         if (p > 0) pxr::k_radix_hist<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, g.chunk);
-        pxr::k_radix_prefix<<<PX_RADIX / 4, 256, 0, stream>>>(sc.hist, g.n_blocks, sc.totals);
-        pxr::k_radix_scatter<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, sc.totals, g.chunk);
+        const int own = g.n_blocks <= PX_OWN_PREFIX_BLOCKS ? g.n_blocks : 0;
+        if (!own) pxr::k_radix_prefix<<<PX_RADIX / 4, 256, 0, stream>>>(sc.hist, g.n_blocks, sc.totals);
+        pxr::k_radix_scatter<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, sc.totals, g.chunk, own);
         uint64_t* t = src;
         src = dst;
         dst = t;

@@ -47,6 +47,9 @@ enum {
     PX_SORT_MAX_BLOCKS = 512,     // multiple of 64
     PX_RADIX = 256
 };
+#ifndef PX_OWN_PREFIX_BLOCKS
+#define PX_OWN_PREFIX_BLOCKS 32   // up to this many blocks a scatter block sums the histogram rows itself
+#endif
 
 struct px_sort_geom {
     int n_blocks;      // blocks of a pass

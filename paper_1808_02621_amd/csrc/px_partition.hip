@@ -74,7 +74,8 @@ extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const in
     const px_sort_geom g = px_sort_geometry(cap);
     ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard, out_offsets};
     pxr::k_radix_hist<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.chunk);
-    pxr::k_radix_prefix<<<PX_RADIX / 4, 256, 0, stream>>>(hist, g.n_blocks, totals);
-    pxr::k_radix_scatter<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, totals, g.chunk);
+    const int own = g.n_blocks <= PX_OWN_PREFIX_BLOCKS ? g.n_blocks : 0;
+    if (!own) pxr::k_radix_prefix<<<PX_RADIX / 4, 256, 0, stream>>>(hist, g.n_blocks, totals);
+    pxr::k_radix_scatter<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, totals, g.chunk, own);
     return px_check_hip(ctx, hipGetLastError(), "partition launch");
 }

@@ -8,6 +8,8 @@
 //            over the blocks and writes the digit's total  -> hist[b][256], totals[256]
 //   scatter  block b scans the totals, adds its own prefix row, then ranks its
 //            chunk tile by tile in LDS and writes every item to its final place.
+// With at most PX_OWN_PREFIX_BLOCKS blocks the prefix kernel is skipped: every scatter block
+// adds up the (few) raw histogram rows itself, which costs less than a launch.
 // Ranking inside a tile is by wave-wide digit matching (ballots), with one LDS
 // counter row per wave, so equal digits keep their input order.
 #ifndef PX_RADIX_H_
@@ -105,10 +107,11 @@ static __global__ __launch_bounds__(256) void k_radix_prefix(uint32_t* __restric
     if (lane == 63) totals[bin] = incl;
 }
 
+// own_prefix_blocks > 0: hist holds the raw counts of that many blocks and totals is not read.
 template <class P>
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const uint32_t* __restrict__ hist,
                                                                    const uint32_t* __restrict__ totals,
-                                                                   int64_t chunk) {
+                                                                   int64_t chunk, int own_prefix_blocks) {
     typedef typename P::Item Item;
     __shared__ Item s_items[PX_SORT_TILE];
     __shared__ uint8_t s_dig[PX_SORT_TILE];
@@ -123,9 +126,22 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
     const uint64_t below = lanes_below();
 
     // Where bin `tid` of this block starts in the output.
-    uint32_t grand;
-    const uint32_t bin_start = block_exclusive_scan_256(totals[tid], s_wave, &grand);
-    uint32_t gpos = bin_start + hist[(size_t) blockIdx.x * PX_RADIX + tid];
+    uint32_t grand, bin_total, before;
+    if (own_prefix_blocks > 0) {
+        bin_total = 0u;
+        before = 0u;
+#pragma unroll 8
+        for (int b = 0; b < own_prefix_blocks; ++b) {
+            const uint32_t c = hist[(size_t) b * PX_RADIX + tid];
+            bin_total += c;
+            before += b < (int) blockIdx.x ? c : 0u;
+        }
+    } else {
+        bin_total = totals[tid];
+        before = hist[(size_t) blockIdx.x * PX_RADIX + tid];
+    }
+    const uint32_t bin_start = block_exclusive_scan_256(bin_total, s_wave, &grand);
+    uint32_t gpos = bin_start + before;
     if (blockIdx.x == 0) p.publish(tid, bin_start, grand);
 
     const int64_t n = p.count();
