@@ -193,6 +193,42 @@ def test_random_shapes(gpu, seed):
               float(rng.choice([0.01, 0.5])), table, accum, scale=scale)
 
 
+RUN_LENGTHS = [1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 24, 31, 32, 33, 40, 63, 64, 65, 96, 127, 128, 129, 255, 257, 300]
+
+
+@pytest.mark.parametrize("dim,bf16", [(128, False), (1024, True), (2048, False), (5, False), (40, True)])
+def test_run_lengths_around_batch_and_window_borders(gpu, dim, bf16):
+    """Runs whose lengths sit on and around the batch sizes (2, 4, 8) and the window sizes (32 ... 256),
+    one run of several thousand rows in the middle, integer values: every row sum must be exact."""
+    rng = np.random.default_rng(77 + dim)
+    lengths = RUN_LENGTHS * 2 + [5000] + RUN_LENGTHS[::-1] * 2 + [1] * 700
+    vocab = 4 * len(lengths)
+    ids_of_runs = np.sort(rng.choice(vocab, size=len(lengths), replace=False))
+    all_ids = np.repeat(ids_of_runs, lengths)
+    rng.shuffle(all_ids)
+    cuts = np.sort(rng.choice(all_ids.size, size=6, replace=False))
+    idx = [a.astype(np.int64) for a in np.split(all_ids, cuts)]
+    val = [inputs.small_integer_values(rng, (i.size, dim)) for i in idx]
+    if bf16:
+        val = [inputs.f32_to_bf16_bits(v) for v in val]
+    table = (rng.standard_normal((vocab, dim)) * 0.02).astype(np.float32)
+    accum = np.full((vocab, dim), 0.1, dtype=np.float32)
+    b, u = run_chain(gpu, idx, val, dim, vocab, 5, "mul", "adagrad", 0.1, table, accum, check_rows_exact=True)
+    assert u == len(lengths)
+
+
+@pytest.mark.parametrize("rows", [65_536, 65_537, 2048 * 33, 2048 * 40 + 1])
+def test_row_counts_around_the_one_launch_prefix_limit(gpu, rows):
+    """Up to 32 sort blocks the scatter sums the histogram rows itself; above, the prefix kernel runs."""
+    rng = np.random.default_rng(rows)
+    vocab, dim = 70_000, 4
+    sizes = rng.multinomial(rows, np.ones(3) / 3)
+    idx = [inputs.draw_ids(rng, vocab, 1.0, int(k)) for k in sizes]
+    val = [inputs.small_integer_values(rng, (int(k), dim)) for k in sizes]
+    table = (rng.standard_normal((vocab, dim)) * 0.02).astype(np.float32)
+    run_chain(gpu, idx, val, dim, vocab, 16, "mod", "sgd", 0.5, table, check_rows_exact=True)
+
+
 def test_unaligned_value_pointers(gpu):
     """Value rows that start 4 bytes into an allocation take the element-wise path."""
     ctx, px, runner = gpu
