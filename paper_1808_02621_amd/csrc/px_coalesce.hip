@@ -139,6 +139,10 @@ inline Scratch carve(void* base, int64_t m, int64_t dim) {
     return s;
 }
 
+// Addresses carried as integers are turned into pointers that name the global address space, so
+// that the loads are global (not flat) instructions.
+#define PX_GLOBAL __attribute__((address_space(1)))
+
 __device__ __forceinline__ uint32_t key_of(uint64_t w) { return (uint32_t) (w >> 32); }
 
 // ---------------------------------------------------------------------- pack
@@ -173,21 +177,42 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__
     const int64_t begin = (int64_t) blockIdx.x * chunk;
     int64_t end = begin + chunk;
     if (end > m) end = m;
-    for (int64_t p = begin + tid; p < end; p += PX_SORT_THREADS) {
-        int lo = 0, hi = n_workers;                 // s_prefix[lo] <= p < s_prefix[hi]
-        while (hi - lo > 1) {
-            int mid = (lo + hi) >> 1;
-            if ((int64_t) s_prefix[mid] <= p) lo = mid; else hi = mid;
+    // PX_SORT_ITEMS rows per thread at a time: their ids are requested together
+    for (int64_t p0 = begin + tid; p0 < end; p0 += (int64_t) PX_SORT_THREADS * PX_SORT_ITEMS) {
+        uint32_t local[PX_SORT_ITEMS];
+        int src[PX_SORT_ITEMS];
+        int64_t id[PX_SORT_ITEMS];
+#pragma unroll
+        for (int j = 0; j < PX_SORT_ITEMS; ++j) {
+            const int64_t p = p0 + (int64_t) j * PX_SORT_THREADS;
+            id[j] = 0;
+            src[j] = 0;
+            local[j] = 0u;
+            if (p < end) {
+                int lo = 0, hi = n_workers;             // s_prefix[lo] <= p < s_prefix[hi]
+                while (hi - lo > 1) {
+                    int mid = (lo + hi) >> 1;
+                    if ((int64_t) s_prefix[mid] <= p) lo = mid; else hi = mid;
+                }
+                src[j] = lo;
+                local[j] = (uint32_t) (p - (int64_t) s_prefix[lo]);
+                const PX_GLOBAL int64_t* ids = (const PX_GLOBAL int64_t*) (CARRIED ? s_idx[lo] : words[lo]);
+                id[j] = ids[local[j]];
+            }
         }
-        const uint32_t local = (uint32_t) (p - (int64_t) s_prefix[lo]);
-        const int64_t* ids = (const int64_t*) (CARRIED ? s_idx[lo] : words[lo]);
-        int64_t id = ids[local];
-        if (id < 0 || id >= vocab) {
-            atomicOr(flags, (uint32_t) PXF_BAD_ID);
-            id = 0;
+#pragma unroll
+        for (int j = 0; j < PX_SORT_ITEMS; ++j) {
+            const int64_t p = p0 + (int64_t) j * PX_SORT_THREADS;
+            if (p < end) {
+                int64_t v = id[j];
+                if (v < 0 || v >= vocab) {
+                    atomicOr(flags, (uint32_t) PXF_BAD_ID);
+                    v = 0;
+                }
+                keys[p] = ((uint64_t) (uint32_t) v << 32) | (uint64_t) (((uint32_t) src[j] << local_bits) | local[j]);
+                atomicAdd(&s_hist[(uint32_t) v & 255u], 1u);
+            }
         }
-        keys[p] = ((uint64_t) (uint32_t) id << 32) | (uint64_t) (((uint32_t) lo << local_bits) | local);
-        atomicAdd(&s_hist[(uint32_t) id & 255u], 1u);
     }
     __syncthreads();
     hist[(size_t) blockIdx.x * PX_RADIX + tid] = s_hist[tid];
@@ -347,9 +372,7 @@ __global__ void k_write_zero_count(int64_t* out_num_unique) {
 typedef PX_SEG_ACC seg_acc_t;
 
 typedef uint32_t seg_v4u __attribute__((ext_vector_type(4)));
-// Value rows are read exactly once, through addresses that were carried as integers: the loads
-// name the global address space so that they are global (not flat) instructions.
-#define PX_GLOBAL __attribute__((address_space(1)))
+// Value rows are read exactly once.
 __device__ __forceinline__ uint4 seg_load16(const char* p) {
     const PX_GLOBAL seg_v4u* g = (const PX_GLOBAL seg_v4u*) (uintptr_t) p;
 #ifdef PX_SEG_TEMPORAL

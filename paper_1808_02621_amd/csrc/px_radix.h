@@ -71,10 +71,23 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_hist(P p, uint32_t* _
     const int64_t begin = (int64_t) blockIdx.x * chunk;
     int64_t end = begin + chunk;
     if (end > n) end = n;
-    for (int64_t i = begin + tid; i < end; i += PX_SORT_THREADS) {
-        uint32_t d = p.digit(p.load(i), i);
-        p.note(i, d);
-        atomicAdd(&s_hist[d], 1u);
+    // PX_SORT_ITEMS items per thread at a time: their loads are requested together
+    for (int64_t i0 = begin + tid; i0 < end; i0 += (int64_t) PX_SORT_THREADS * PX_SORT_ITEMS) {
+        typename P::Item v[PX_SORT_ITEMS];
+#pragma unroll
+        for (int j = 0; j < PX_SORT_ITEMS; ++j) {
+            const int64_t i = i0 + (int64_t) j * PX_SORT_THREADS;
+            v[j] = i < end ? p.load(i) : typename P::Item(0);
+        }
+#pragma unroll
+        for (int j = 0; j < PX_SORT_ITEMS; ++j) {
+            const int64_t i = i0 + (int64_t) j * PX_SORT_THREADS;
+            if (i < end) {
+                uint32_t d = p.digit(v[j], i);
+                p.note(i, d);
+                atomicAdd(&s_hist[d], 1u);
+            }
+        }
     }
     __syncthreads();
     hist[(size_t) blockIdx.x * PX_RADIX + tid] = s_hist[tid];
