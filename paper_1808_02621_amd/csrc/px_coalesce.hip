@@ -6,7 +6,9 @@
 //   2. sort    stable least-significant-digit radix sort of the words on the id bits only
 //              (ceil(log2 vocab) bits, 8 per pass); value rows never move
 //   3. heads   a row is a run head if its id differs from its predecessor's; counting and
-//              ranking the heads yields U, the distinct ids and every run's start
+//              ranking the heads yields U, the distinct ids and every run's start.  Every sorted
+//              word is also turned into a row reference: the address of its value row, with
+//              bit 0 set on the last row of a run
 //   4. segsum  the sorted order is cut into windows of T rows; tile t starts at the first head
 //              in the leading quarter of window t (else at the window's own border) and ends
 //              where tile t+1 starts, so the short runs that dominate never straddle two tiles
