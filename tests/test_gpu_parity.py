@@ -153,6 +153,53 @@ def test_stress_full_size(gpu):
     run_workload(gpu, inputs.STRESS_ZIPF)
 
 
+def test_contexts_on_separate_streams_give_the_same_bits(gpu):
+    """Two variables' chains and a dense mean enqueued side by side, one context and stream each."""
+    ctx, px, runner = gpu
+    w = inputs.shrink(inputs.NMT, n_workers=12, n_per_worker=3000, dense_count=1 << 20)
+    hash_code = px.PX_HASH_MUL
+    tables0 = [inputs.table_init(w, t) for t in range(2)]
+    dev = []
+    for t in range(2):
+        d_idx = [runner.to_device(i) for i in inputs.sparse_ids(w, t)]
+        d_val = [runner.to_device(v) for v in inputs.sparse_values(w, t)]
+        dev.append((d_idx, d_val))
+    d_dense = [runner.to_device(b) for b in inputs.dense_buffers(w)]
+
+    def run(contexts, streams):
+        outs = []
+        bufs = [runner.sparse_buffers(i, v, w.dim, w.vocab, w.n_shards, hash_code) for i, v in dev]
+        tabs = [torch.from_numpy(t0).cuda() for t0 in tables0]
+        mean = torch.empty(w.dense_count, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        contexts[2].px_dense_average(d_dense, w.dense_count, mean, 1.0 / w.n_workers, streams[2])
+        for t in range(2):
+            runner.sparse_step(contexts[t], bufs[t], tabs[t], None, "sgd", w.lr, stream=streams[t])
+        torch.cuda.synchronize()
+        for c in set(contexts):
+            assert c.px_device_status() == px.PX_OK
+        for t in range(2):
+            u = int(bufs[t].out_num.item())
+            outs += [bufs[t].out_ids[:u].clone(), bufs[t].out_rows[:u].clone(), bufs[t].perm[:u].clone(), tabs[t]]
+        return outs + [mean]
+
+    serial = run([ctx, ctx, ctx], [None, None, None])
+    side_ctx = [px.Context(0) for _ in range(3)]
+    side_streams = [torch.cuda.Stream() for _ in range(3)]
+    try:
+        for _ in range(3):
+            for a, b in zip(serial, run(side_ctx, side_streams)):
+                assert torch.equal(a, b)
+    finally:
+        for c in side_ctx:
+            c.close()
+    # and the serial result is the oracle's
+    o_ids, o_rows, _ = oracle.sparse_coalesce(inputs.sparse_ids(w, 0), inputs.sparse_values(w, 0), w.dim, w.vocab)
+    assert np.array_equal(serial[0].cpu().numpy(), o_ids)
+    close(serial[1].cpu().numpy(), o_rows)
+    close(serial[8].cpu().numpy(), oracle.dense_average(inputs.dense_buffers(w), average=True))
+
+
 # ------------------------------------------------------------------- shapes
 
 @pytest.mark.parametrize("dim", [1, 3, 7, 8, 20, 64, 100, 132, 300, 1028, 2052])
