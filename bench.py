@@ -254,6 +254,45 @@ def partition_search(torch, px, dw, p_start=8, p_max=256):
     return out
 
 
+# ------------------------------------------------------------- sparsity sweep
+
+SWEEP_VOCAB = 50_000
+SWEEP_LENGTHS = (120, 60, 30, 15, 8, 4, 1)
+
+
+def sparsity_sweep(torch, px, ctx, base):
+    """The analogue of the paper's Table 6 on this path: the Large-vocab LM recipe at a smaller, fixed
+    vocabulary, ids per worker = length x 128 (the paper's batch), one sparse chain timed per length.
+    alpha is the fraction of the table's rows a worker's mini-batch touches (Sec. 2.2)."""
+    import dataclasses
+    from paper_1808_02621_amd import inputs, runner
+    out = []
+    for length in SWEEP_LENGTHS:
+        w = dataclasses.replace(base, name="sparsity_sweep", vocab=SWEEP_VOCAB, n_per_worker=length * 128,
+                                n_tables=1, dense_count=0)
+        idx = inputs.sparse_ids(w, 0)
+        m, u, longest, alpha = inputs.id_statistics(idx, w.vocab)
+        d_idx = [runner.to_device(i) for i in idx]
+        d_val = [torch.randn((i.numel(), w.dim), dtype=torch.float32, device="cuda") for i in d_idx]   # timing only
+        b = runner.sparse_buffers(d_idx, d_val, w.dim, w.vocab, w.n_shards, px.PX_HASH_MUL)
+        table = torch.zeros((w.vocab, w.dim), dtype=torch.float32, device="cuda")
+        accum = torch.full((w.vocab, w.dim), w.accum_init, dtype=torch.float32, device="cuda")
+
+        def chain(b=b, table=table, accum=accum, w=w):
+            runner.sparse_step(ctx, b, table, accum, w.optimizer, w.lr)
+
+        avg, mn = event_timed(torch, chain, 20, 4)
+        assert int(b.out_num.item()) == u
+        nbytes = sum(sparse_bytes(m, u, w.dim, 4, w.n_shards, w.optimizer))
+        out.append({"length": length, "rows_per_worker": length * 128, "input_rows": m, "unique_rows": u,
+                    "alpha_worker": alpha, "alpha_all_workers": u / w.vocab, "chain_avg_us": avg * 1e6,
+                    "rows_per_s": m / avg, "frac": nbytes / avg / 1e9 / HBM_PEAK_GBPS})
+        del b, table, accum, d_val, d_idx
+        torch.cuda.empty_cache()
+    return {"what": "Large-vocab LM recipe at vocab %d, 48 workers, ids per worker = length x 128" % SWEEP_VOCAB,
+            "points": out}
+
+
 # -------------------------------------------------------------- CPU baseline
 
 def cpu_baseline(dw):
@@ -445,6 +484,7 @@ def main():
 
                 t2, _ = event_timed(torch, two_level, 10, 2)
                 t1, _ = event_timed(torch, one_level, 10, 2)
+                entry["sparsity_sweep"] = sparsity_sweep(torch, px, ctx, ow)
                 entry["two_level_aggregation"] = {
                     "what": "coalesce per group of 6 workers, read the 8 counts back, coalesce the 8 results "
                             "(allocations included) vs one coalesce of all 48",
