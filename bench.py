@@ -254,6 +254,41 @@ def partition_search(torch, px, dw, p_start=8, p_max=256):
     return out
 
 
+# ------------------------------------------------------------ per-call times
+
+def per_call(torch, dw, steps, warmup):
+    """Mean duration, achieved GB/s and fraction of peak of each of the three sparse calls
+    (all tables of the workload together), from event pairs around each call."""
+    w, r = dw.w, dw.runner
+    names = ("coalesce", "partition", "apply")
+    pairs = {n: [] for n in names}
+    for it in range(warmup + steps):
+        for t in range(w.n_tables):
+            b = dw.bufs[t][dw.step_no % len(dw.bufs[t])]
+            calls = (lambda: r.coalesce(dw.ctx, b), lambda: r.partition(dw.ctx, b),
+                     lambda: r.apply(dw.ctx, b, dw.tables[t], dw.accums[t], w.optimizer, w.lr))
+            for n, call in zip(names, calls):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                call()
+                e1.record()
+                if it >= warmup:
+                    pairs[n].append((t, e0, e1))
+        dw.step_no += 1
+    torch.cuda.synchronize()
+    es = 2 if w.val_dtype == "bf16" else 4
+    alg = [0, 0, 0]
+    for u in dw.unique_counts():
+        for i, x in enumerate(sparse_bytes(w.total_rows, u, w.dim, es, w.n_shards, w.optimizer)):
+            alg[i] += x
+    out = {}
+    for i, n in enumerate(names):
+        per_step = sum(e0.elapsed_time(e1) for _, e0, e1 in pairs[n]) * 1e-3 / steps
+        out[n] = {"avg_us": per_step * 1e6, "algorithmic_bytes": alg[i], "achieved_gbps": alg[i] / per_step / 1e9,
+                  "frac": alg[i] / per_step / 1e9 / HBM_PEAK_GBPS}
+    return out
+
+
 # ------------------------------------------------------------- sparsity sweep
 
 SWEEP_VOCAB = 50_000
@@ -295,36 +330,61 @@ def sparsity_sweep(torch, px, ctx, base):
 
 # -------------------------------------------------------------- CPU baseline
 
-def cpu_baseline(dw):
-    """The oracle, as it stands, on one host core: the whole sparse chain of every table plus
-    the dense mean on a 1/16 slice of each buffer (scaled up), as rows per second of a step."""
+def cpu_baseline(dw, sparse_budget_s=5.0, dense_budget_s=5.0):
+    """The oracle, as it stands, on one host core: the whole sparse chain of every table, repeated
+    until about sparse_budget_s of CPU time is spent, plus the dense mean on a leading slice of
+    every buffer sized for about dense_budget_s (scaled up to the whole buffer), as rows per second
+    of a step.  Tables are allocated outside the timed region."""
     import oracle
     w = dw.w
-    t0 = time.perf_counter()
-    for t in range(w.n_tables):
-        ids, rows, _ = oracle.sparse_coalesce(dw.host_idx[t], dw.host_val[t], w.dim, w.vocab)
-        _, perm, _ = oracle.partition_rows(ids, w.n_shards, w.hash)
-        table = np.zeros((w.vocab, w.dim), dtype=np.float32)
-        if w.optimizer == "sgd":
-            oracle.sparse_apply_sgd(table, ids, rows, w.lr, perm=perm)
-        else:
-            oracle.sparse_apply_adagrad(table, np.full_like(table, w.accum_init), ids, rows, w.lr, perm=perm)
-    t_sparse = time.perf_counter() - t0
-    t_dense, frac = 0.0, 16
-    if dw.dense:
-        n = w.dense_count // frac
-        host = [d[:n].view(dw.torch.int16).cpu().numpy().view(np.uint16) if w.dense_dtype == "bf16"
-                else d[:n].cpu().numpy() for d in dw.dense]
+    tables = [np.zeros((w.vocab, w.dim), dtype=np.float32) for _ in range(w.n_tables)]
+    accums = [np.full((w.vocab, w.dim), w.accum_init, dtype=np.float32) if w.optimizer == "adagrad" else None
+              for _ in range(w.n_tables)]
+    reps, t_sparse_all = 0, 0.0
+    while reps < 1 or (t_sparse_all < sparse_budget_s and reps < 50):
         t0 = time.perf_counter()
-        oracle.dense_average(host, average=True)
-        t_dense = (time.perf_counter() - t0) * frac
+        for t in range(w.n_tables):
+            ids, rows, _ = oracle.sparse_coalesce(dw.host_idx[t], dw.host_val[t], w.dim, w.vocab)
+            _, perm, _ = oracle.partition_rows(ids, w.n_shards, w.hash)
+            if w.optimizer == "sgd":
+                oracle.sparse_apply_sgd(tables[t], ids, rows, w.lr, perm=perm)
+            else:
+                oracle.sparse_apply_adagrad(tables[t], accums[t], ids, rows, w.lr, perm=perm)
+        t_sparse_all += time.perf_counter() - t0
+        reps += 1
+    t_sparse = t_sparse_all / reps
+    t_dense, dense_note = 0.0, "no dense part"
+    if dw.dense:
+        def slice_time(n):
+            host = [d[:n].view(dw.torch.int16).cpu().numpy().view(np.uint16) if w.dense_dtype == "bf16"
+                    else d[:n].cpu().numpy() for d in dw.dense]
+            t0 = time.perf_counter()
+            oracle.dense_average(host, average=True)
+            return time.perf_counter() - t0
+        probe_n = max(1, w.dense_count // 64)
+        probe = slice_time(probe_n)                               # sizes the real sample
+        n = int(min(w.dense_count, max(probe_n, probe_n * dense_budget_s / max(probe, 1e-6))))
+        spent = slice_time(n)
+        t_dense = spent * w.dense_count / n
+        dense_note = "dense mean on the first %d of %d elements of every buffer (%.2f s), scaled to the whole" % (
+            n, w.dense_count, spent)
     total = t_sparse + t_dense
     return {
         "value": w.n_tables * w.total_rows / total, "unit": "rows/s", "cores": 1, "kind": "oracle",
-        "sample": "full sparse chain of %d table(s) (%.2f s) + dense mean on 1/%d of each buffer, scaled x%d "
-                  "(%.2f s)" % (w.n_tables, t_sparse, frac, frac, t_dense),
-        "seconds_per_step": total,
+        "sample": "full sparse chain of %d table(s), %d repetitions (%.2f s in all, %.3f s each) + %s"
+                  % (w.n_tables, reps, t_sparse_all, t_sparse, dense_note),
+        "seconds_per_step": total, "host_cpus": os.cpu_count(), "cpu_model": cpu_model(),
     }
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 # ---------------------------------------------------------------------- main
@@ -407,6 +467,11 @@ def main():
         "rows_per_s": rows_per_step / sparse_avg,
     }
 
+    result["sparse_chain"]["unique_rows_per_s"] = sum(uniq) / sparse_avg
+    result["sparse_calls"] = per_call(torch, dw, max(5, args.steps // 2), 2)
+    if dw.dense:
+        result["roofline"]["elements_per_s"] = w.dense_count / (result["roofline"]["avg_call_us"] * 1e-6)
+
     fused_avg, fused_min = event_timed(torch, dw.sparse_fused, max(5, args.steps // 2), 2)
     result["sparse_chain_fused"] = {
         "what": "px_sparse_coalesce_apply_* + px_partition_rows: same result, aggregated rows never stored",
@@ -468,7 +533,8 @@ def main():
 
             s_avg, s_min = event_timed(torch, sparse_rot, 20, 4)
             f_avg, f_min = event_timed(torch, fused_rot, 20, 4)
-            entry = {"unique_rows": odw.unique_counts(), "sparse_avg_us": s_avg * 1e6, "sparse_min_us": s_min * 1e6,
+            entry = {"unique_rows": odw.unique_counts(), "sparse_calls": per_call(torch, odw, 10, 2),
+                     "sparse_avg_us": s_avg * 1e6, "sparse_min_us": s_min * 1e6,
                      "sparse_gbps": obytes / s_avg / 1e9, "sparse_frac": obytes / s_avg / 1e9 / HBM_PEAK_GBPS,
                      "rows_per_s": ow.n_tables * ow.total_rows / s_avg,
                      "fused_avg_us": f_avg * 1e6, "fused_frac_unfused_bytes": obytes / f_avg / 1e9 / HBM_PEAK_GBPS}
