@@ -618,6 +618,34 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
         // row j of the current batch is the last of run u
         auto finish = [&](int j) {
             if (!FUSED) {
+#ifndef PX_SEG_NO_EXCHANGE
+                if (VEC && E == 8) {
+                    // A piece of 8 bfloat16 becomes 32 bytes of output.  Lanes trade halves so that each
+                    // store instruction writes one contiguous block of G*16 bytes: in store h lane l
+                    // writes half (l & 1) of piece h*G/2 + l/2 of the lane group's block.
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        float o[8];
+#pragma unroll
+                        for (int x = 0; x < 8; ++x) o[x] = (float) ((double) acc[c][x < E ? x : 0] * a.scale);
+#pragma unroll
+                        for (int hh = 0; hh < 2; ++hh) {
+                            const int src = hh * (G / 2) + (gl >> 1);
+                            float lo[4], hi[4];
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) {
+                                lo[x] = __shfl(o[x], src, G);
+                                hi[x] = __shfl(o[4 + x], src, G);
+                            }
+                            const bool odd = (gl & 1) != 0;
+                            const float4 v = make_float4(odd ? hi[0] : lo[0], odd ? hi[1] : lo[1], odd ? hi[2] : lo[2],
+                                                         odd ? hi[3] : lo[3]);
+                            if ((int) blockIdx.y * (G * C) + c * G + src < a.pieces)
+                                seg_store16(dst + (size_t) c * (G * 8) + hh * (G * 4) - gl * 4, v);
+                        }
+                    }
+                } else
+#endif
 #pragma unroll
                 for (int c = 0; c < C; ++c)
                     if (live[c]) {
