@@ -801,6 +801,12 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
 //               the 16 sums are added in wave order
 //   other runs  one wave per run and slab
 enum { FIX_SPLITS = 16 };
+#ifndef PX_FIXUP_DEPTH
+#define PX_FIXUP_DEPTH 8         // partial rows a wave of a long run's workgroup requests at a time
+#endif
+#ifndef PX_FIXUP_RESIDENT
+#define PX_FIXUP_RESIDENT 256    // workgroups of 16 waves in one fix-up launch (measured: 128 and 512 are slower)
+#endif
 
 struct FixupArgs {
     int mode;                     // MODE_ROWS, MODE_SGD or MODE_ADAGRAD
@@ -898,21 +904,21 @@ __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
         double acc = 0.0;
         if (live) {
             uint32_t q = split;
-            for (; q + 7 * FIX_SPLITS < pl.parts; q += 8 * FIX_SPLITS) {
-                double v[8];
+            for (; q + (PX_FIXUP_DEPTH - 1) * FIX_SPLITS < pl.parts; q += PX_FIXUP_DEPTH * FIX_SPLITS) {
+                double v[PX_FIXUP_DEPTH];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = pl.row(q + j * FIX_SPLITS, a.pfirst, a.plast, a.pstride)[pe];
+                for (int j = 0; j < PX_FIXUP_DEPTH; ++j) v[j] = pl.row(q + j * FIX_SPLITS, a.pfirst, a.plast, a.pstride)[pe];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc += v[j];
+                for (int j = 0; j < PX_FIXUP_DEPTH; ++j) acc += v[j];
             }
             {
-                // at most seven parts are left for this wave: request them together, add them in order
-                double v[7];
+                // fewer than a full batch is left for this wave: request them together, add them in order
+                double v[PX_FIXUP_DEPTH - 1];
 #pragma unroll
-                for (int j = 0; j < 7; ++j)
+                for (int j = 0; j < PX_FIXUP_DEPTH - 1; ++j)
                     v[j] = q + j * FIX_SPLITS < pl.parts ? pl.row(q + j * FIX_SPLITS, a.pfirst, a.plast, a.pstride)[pe] : 0.0;
 #pragma unroll
-                for (int j = 0; j < 7; ++j)
+                for (int j = 0; j < PX_FIXUP_DEPTH - 1; ++j)
                     if (q + j * FIX_SPLITS < pl.parts) acc += v[j];
             }
         }
@@ -1172,8 +1178,14 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
     f.E = sh.E;
     f.pieces = sh.pieces;
     f.scale = scale;
-    const unsigned fx = (unsigned) (n_tiles < 64 ? n_tiles : 64);
-    k_fixup<<<dim3(fx, (unsigned) ((sh.pstride + 63) / 64), 1), 64 * FIX_SPLITS, 0, stream>>>(f);
+    // 1,024-thread workgroups: the grid stays at one per compute unit, so that all of them are resident
+    // at once (a second round of workgroups would only start after the first one's long runs)
+    const unsigned fy = (unsigned) ((sh.pstride + 63) / 64);
+    unsigned fx = PX_FIXUP_RESIDENT / fy;
+    if (fx > 64u) fx = 64u;
+    if (fx < 8u) fx = 8u;
+    if ((int64_t) fx > n_tiles) fx = (unsigned) n_tiles;
+    k_fixup<<<dim3(fx, fy, 1), 64 * FIX_SPLITS, 0, stream>>>(f);
     return px_check_hip(ctx, hipGetLastError(), "coalesce launch");
 }
 
