@@ -1,6 +1,6 @@
 """Benchmark of the sparse/dense gradient aggregation hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others] [--no-cpu] [--separate-streams]
 
 A step is one pass of the whole hot path over one batch of synthetic gradients:
 for every sparse variable coalesce -> partition -> apply, then the dense mean.
@@ -38,6 +38,9 @@ def parse_args():
     ap.add_argument("--workload", default="nmt_like")
     ap.add_argument("--no-others", action="store_true", help="skip the brief runs of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--separate-streams", action="store_true",
+                    help="also time the step with the tables and the dense mean on their own streams (kernels "
+                         "then overlap, so leave it out of runs whose per-kernel durations are read)")
     return ap.parse_args()
 
 
@@ -482,23 +485,24 @@ def main():
     }
     # the same step with the independent pieces on their own streams: reported beside the headline,
     # which stays on one stream so that every kernel's duration is its own
-    dw.overlapped_setup()
-    for _ in range(2):
-        dw.step_overlapped()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(max(5, args.steps // 2)):
-        dw.step_overlapped()
-    torch.cuda.synchronize()
-    over = (time.perf_counter() - t0) / max(5, args.steps // 2)
-    for c in dw.side_ctx:
-        assert c.px_device_status() == px.PX_OK
-    result["step_on_separate_streams"] = {
-        "what": "the tables' chains and the dense mean enqueued on %d streams (one context each), same results"
-                % len(dw.side_streams),
-        "ms_per_step": over * 1e3, "rows_per_s": rows_per_step / over,
-        "step_hbm_frac": (sp_bytes + dn_bytes) / over / 1e9 / HBM_PEAK_GBPS,
-    }
+    if args.separate_streams:
+        dw.overlapped_setup()
+        for _ in range(2):
+            dw.step_overlapped()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(max(5, args.steps // 2)):
+            dw.step_overlapped()
+        torch.cuda.synchronize()
+        over = (time.perf_counter() - t0) / max(5, args.steps // 2)
+        for c in dw.side_ctx:
+            assert c.px_device_status() == px.PX_OK
+        result["step_on_separate_streams"] = {
+            "what": "the tables' chains and the dense mean enqueued on %d streams (one context each), same results"
+                    % len(dw.side_streams),
+            "ms_per_step": over * 1e3, "rows_per_s": rows_per_step / over,
+            "step_hbm_frac": (sp_bytes + dn_bytes) / over / 1e9 / HBM_PEAK_GBPS,
+        }
     dw.pull_setup()
     pull_avg, pull_min = event_timed(torch, dw.pull, max(5, args.steps // 2), 2)
     result["pull_side"] = {
