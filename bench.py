@@ -452,9 +452,9 @@ def main():
     if dense_pairs:
         ms = [a.elapsed_time(b) for a, b in dense_pairs]
         avg = float(np.mean(ms)) * 1e-3
-        # px_dense_average cuts an output above 32 MiB into launches of 8 MiB of output each
+        # px_dense_average cuts an output above 8 MiB into launches of 8 MiB of output each
         out_bytes = w.dense_count * 4
-        launches = -(-out_bytes // (8 << 20)) if out_bytes > (32 << 20) else 1
+        launches = -(-out_bytes // (8 << 20))
         traffic = measured_traffic("k_dense_vec", w.name)
         result["roofline"] = {
             "kernel": "k_dense_vec (px_dense_average, %d launches per call)" % launches, "bound": "hbm",

@@ -203,7 +203,7 @@ px_status px_sparse_coalesce_apply_adagrad(px_ctx* ctx, int n_workers, const int
  *   bufs   host array of n_buffers dev pointers, each in_dtype[count]
  *   out    dev out_dtype[count]; may alias none of the inputs
  * Accumulation is in worker order, in double precision, rounded once.
- * Outputs above 32 MiB are produced by several kernel launches of 8 MiB of output each.
+ * Outputs above 8 MiB are produced by several kernel launches of 8 MiB of output each.
  * Limits: 1 <= n_buffers <= PX_MAX_SOURCES.  Pointers aligned to the element
  * size; 16-byte alignment selects the 128-bit path.
  */

@@ -79,7 +79,12 @@ __global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ 
                                                    int n_buffers, int64_t first, int64_t pieces,
                                                    void* __restrict__ out, float scale) {
     enum { E = In<TIN>::E };
-    const int64_t i = first + (int64_t) blockIdx.x * 256 + threadIdx.x;
+#ifndef PX_DENSE_PLAIN_BLOCKS
+    const unsigned lb = px_die_contiguous_block(blockIdx.x, gridDim.x);    // the grid is a multiple of 8
+#else
+    const unsigned lb = blockIdx.x;
+#endif
+    const int64_t i = first + (int64_t) lb * 256 + threadIdx.x;
     if (i >= pieces) return;
     const uint4* const* bufs = (const uint4* const*) (CARRIED ? pack.w : words);
     acc_t acc[E];
@@ -146,11 +151,11 @@ void launch(px_ctx* ctx, const px_word_pack& pack, int n, int64_t count, bool ve
         const int64_t pieces = count / E;
         const int64_t out_piece_bytes = E * (OUT_BF16 ? 2 : 4);
         int64_t per_launch = pieces;
-        if (PX_DENSE_CHUNK_MB > 0 && pieces * out_piece_bytes > 4 * ((int64_t) PX_DENSE_CHUNK_MB << 20))
+        if (PX_DENSE_CHUNK_MB > 0 && pieces * out_piece_bytes > ((int64_t) PX_DENSE_CHUNK_MB << 20))
             per_launch = ((int64_t) PX_DENSE_CHUNK_MB << 20) / out_piece_bytes;     // measured: 8 MiB best of 4..16
         for (int64_t first = 0; first < pieces; first += per_launch) {
             const int64_t last = first + per_launch < pieces ? first + per_launch : pieces;
-            k_dense_vec<TIN, OUT_BF16, CARRIED><<<(unsigned) ((last - first + 255) / 256), 256, 0, stream>>>(
+            k_dense_vec<TIN, OUT_BF16, CARRIED><<<px_round_up_8((unsigned) ((last - first + 255) / 256)), 256, 0, stream>>>(
                 ctx->d_words, pack, n, first, last, out, scale);
         }
         done = pieces * E;

@@ -66,4 +66,17 @@ static inline px_sort_geom px_sort_geometry(int64_t n) {
     return g;
 }
 
+// Workgroups are handed to the chip's 8 dies (each with its own L2) in turn, so consecutive
+// workgroup numbers land on different dies.  A streaming kernel that gives workgroup b the b-th
+// few-KB piece of a buffer therefore has every die touch every 8th piece, which concentrates its
+// traffic on a few of its L2 channels.  This maps the hardware's workgroup number to a logical one
+// such that each die works on one contiguous eighth of the grid.  The grid must be a multiple of 8
+// (round it up; surplus workgroups find nothing to do).
+#ifdef __HIPCC__
+__device__ __forceinline__ unsigned px_die_contiguous_block(unsigned b, unsigned n_blocks) {
+    return (b & 7u) * (n_blocks >> 3) + (b >> 3);
+}
+#endif
+static inline unsigned px_round_up_8(unsigned n) { return (n + 7u) & ~7u; }
+
 #endif  // PX_INTERNAL_H_
