@@ -2,9 +2,9 @@
 //
 // Parallax Sec. 2.1: AllReduce computes the sum over the workers of their
 // gradients (Sec. 4.1: or the average); this is the reduction one GPU performs
-// on the slice it owns.  One streaming pass: each thread owns 16 bytes of every
-// input buffer (4 floats or 8 bfloat16), keeps 4 loads in flight, adds in worker
-// order and writes once.  Pure HBM streaming: N*C*es bytes in, C*4 (or C*2) out.
+// on the slice it owns.  One streaming pass: each thread owns four 16-byte pieces of
+// every input buffer (4 floats or 8 bfloat16 each), reads them from two buffers at a
+// time, adds in worker order and writes once.  Pure HBM streaming: N*C*es bytes in, C*4 (or C*2) out.
 #include <string.h>
 
 #include "px_internal.h"
@@ -18,9 +18,12 @@ typedef double acc_t;
 #endif
 
 #ifndef PX_DENSE_BATCH
-#define PX_DENSE_BATCH 4        // loads in flight per thread (measured: 3..5 beat 2 and 6..24 by 2-3 %)
+#define PX_DENSE_BATCH 2        // buffers a thread reads from at a time (with 4 pieces each: 8 loads in flight)
 #endif
 enum { DENSE_BATCH = PX_DENSE_BATCH };
+#ifndef PX_DENSE_PIECES
+#define PX_DENSE_PIECES 4       // 16-byte pieces of every buffer per thread, 4 KB apart (measured: 4 x 2 >= 2 x 2 >= 1 x 4 > 1 x 8)
+#endif
 
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
@@ -66,7 +69,8 @@ template <> struct In<uint16_t> {
     static __device__ __forceinline__ float widen(uint16_t v) { return __uint_as_float((uint32_t) v << 16); }
 };
 
-// Thread i owns piece i (16 bytes) of every buffer.
+// A workgroup owns 4 consecutive kilobyte-rows of 256 pieces (16 bytes each) of every buffer; a thread
+// owns one piece of each row.
 #ifndef PX_DENSE_CHUNK_MB
 #define PX_DENSE_CHUNK_MB 8     // output bytes per launch, in MiB (0: one launch for everything)
 #endif
@@ -84,43 +88,64 @@ __global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ 
 #else
     const unsigned lb = blockIdx.x;
 #endif
-    const int64_t i = first + (int64_t) lb * 256 + threadIdx.x;
-    if (i >= pieces) return;
     const uint4* const* bufs = (const uint4* const*) (CARRIED ? pack.w : words);
-    acc_t acc[E];
+    enum { P = PX_DENSE_PIECES };
+    int64_t ip[P];
+    bool okp[P];
 #pragma unroll
-    for (int x = 0; x < E; ++x) acc[x] = (acc_t) 0;
-    for (int w0 = 0; w0 < n_buffers; w0 += DENSE_BATCH) {
-        uint4 r[DENSE_BATCH];
-#pragma unroll
-        for (int j = 0; j < DENSE_BATCH; ++j)
-            if (w0 + j < n_buffers) r[j] = load16(bufs[w0 + j] + i);
-#pragma unroll
-        for (int j = 0; j < DENSE_BATCH; ++j)
-            if (w0 + j < n_buffers) In<TIN>::add(acc, r[j]);
+    for (int q = 0; q < P; ++q) {
+        ip[q] = first + ((int64_t) lb * P + q) * 256 + threadIdx.x;
+        okp[q] = ip[q] < pieces;
+        if (!okp[q]) ip[q] = pieces - 1;
     }
-    float o[E];
+    if (!okp[0]) return;
+    acc_t acc[P][E];
 #pragma unroll
-    for (int x = 0; x < E; ++x) o[x] = (float) (acc[x] * (acc_t) scale);
-    if (OUT_BF16) {
-        uint16_t* dst = (uint16_t*) out + i * E;
-        if constexpr (E == 8) {
-            uint4 v;
-            v.x = to_bf16(o[0]) | ((uint32_t) to_bf16(o[1]) << 16);
-            v.y = to_bf16(o[2]) | ((uint32_t) to_bf16(o[3]) << 16);
-            v.z = to_bf16(o[4]) | ((uint32_t) to_bf16(o[5]) << 16);
-            v.w = to_bf16(o[6]) | ((uint32_t) to_bf16(o[7]) << 16);
-            *(uint4*) dst = v;
+    for (int q = 0; q < P; ++q)
+#pragma unroll
+        for (int x = 0; x < E; ++x) acc[q][x] = (acc_t) 0;
+    for (int w0 = 0; w0 < n_buffers; w0 += DENSE_BATCH) {
+        uint4 r[DENSE_BATCH][P];
+#pragma unroll
+        for (int j = 0; j < DENSE_BATCH; ++j)
+            if (w0 + j < n_buffers) {
+#pragma unroll
+                for (int q = 0; q < P; ++q) r[j][q] = load16(bufs[w0 + j] + ip[q]);
+            }
+#pragma unroll
+        for (int j = 0; j < DENSE_BATCH; ++j)
+            if (w0 + j < n_buffers) {
+#pragma unroll
+                for (int q = 0; q < P; ++q) In<TIN>::add(acc[q], r[j][q]);
+            }
+    }
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+        if (!okp[q]) continue;
+        const int64_t i = ip[q];
+        float o[E];
+#pragma unroll
+        for (int x = 0; x < E; ++x) o[x] = (float) (acc[q][x] * (acc_t) scale);
+        if (OUT_BF16) {
+            uint16_t* dst = (uint16_t*) out + i * E;
+            if constexpr (E == 8) {
+                uint4 v;
+                v.x = to_bf16(o[0]) | ((uint32_t) to_bf16(o[1]) << 16);
+                v.y = to_bf16(o[2]) | ((uint32_t) to_bf16(o[3]) << 16);
+                v.z = to_bf16(o[4]) | ((uint32_t) to_bf16(o[5]) << 16);
+                v.w = to_bf16(o[6]) | ((uint32_t) to_bf16(o[7]) << 16);
+                *(uint4*) dst = v;
+            } else {
+                uint2 v;
+                v.x = to_bf16(o[0]) | ((uint32_t) to_bf16(o[1]) << 16);
+                v.y = to_bf16(o[2]) | ((uint32_t) to_bf16(o[3]) << 16);
+                *(uint2*) dst = v;
+            }
         } else {
-            uint2 v;
-            v.x = to_bf16(o[0]) | ((uint32_t) to_bf16(o[1]) << 16);
-            v.y = to_bf16(o[2]) | ((uint32_t) to_bf16(o[3]) << 16);
-            *(uint2*) dst = v;
-        }
-    } else {
-        float4* dst = (float4*) ((float*) out + i * E);
+            float4* dst = (float4*) ((float*) out + i * E);
 #pragma unroll
-        for (int x = 0; x < E; x += 4) dst[x / 4] = make_float4(o[x], o[x + 1], o[x + 2], o[x + 3]);
+            for (int x = 0; x < E; x += 4) dst[x / 4] = make_float4(o[x], o[x + 1], o[x + 2], o[x + 3]);
+        }
     }
 }
 
@@ -155,7 +180,7 @@ void launch(px_ctx* ctx, const px_word_pack& pack, int n, int64_t count, bool ve
             per_launch = ((int64_t) PX_DENSE_CHUNK_MB << 20) / out_piece_bytes;     // measured: 8 MiB best of 4..16
         for (int64_t first = 0; first < pieces; first += per_launch) {
             const int64_t last = first + per_launch < pieces ? first + per_launch : pieces;
-            k_dense_vec<TIN, OUT_BF16, CARRIED><<<px_round_up_8((unsigned) ((last - first + 255) / 256)), 256, 0, stream>>>(
+            k_dense_vec<TIN, OUT_BF16, CARRIED><<<px_round_up_8((unsigned) ((last - first + 256 * PX_DENSE_PIECES - 1) / (256 * PX_DENSE_PIECES))), 256, 0, stream>>>(
                 ctx->d_words, pack, n, first, last, out, scale);
         }
         done = pieces * E;
