@@ -452,9 +452,8 @@ def main():
     if dense_pairs:
         ms = [a.elapsed_time(b) for a, b in dense_pairs]
         avg = float(np.mean(ms)) * 1e-3
-        # px_dense_average cuts an output above 8 MiB into launches of 8 MiB of output each
-        out_bytes = w.dense_count * 4
-        launches = -(-out_bytes // (8 << 20))
+        # a long output is produced by several launches in a row; the library says how many
+        launches = px.px_dense_average_launches(w.n_workers, w.dense_count, w.dense_dtype == "bf16")
         traffic = measured_traffic("k_dense_vec", w.name)
         result["roofline"] = {
             "kernel": "k_dense_vec (px_dense_average, %d launches per call)" % launches, "bound": "hbm",

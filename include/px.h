@@ -203,13 +203,20 @@ px_status px_sparse_coalesce_apply_adagrad(px_ctx* ctx, int n_workers, const int
  *   bufs   host array of n_buffers dev pointers, each in_dtype[count]
  *   out    dev out_dtype[count]; may alias none of the inputs
  * Accumulation is in worker order, in double precision, rounded once.
- * Outputs above 8 MiB are produced by several kernel launches of 8 MiB of output each.
+ * A long output is produced by several kernel launches in a row (px_dense_average_launches says
+ * how many): each covers 2^19 16-byte pieces of every buffer, more when there are few buffers,
+ * and at most 16 MiB of output.
  * Limits: 1 <= n_buffers <= PX_MAX_SOURCES.  Pointers aligned to the element
  * size; 16-byte alignment selects the 128-bit path.
  */
 px_status px_dense_average(px_ctx* ctx, int n_buffers, const void* const* bufs, int64_t count,
                            px_dtype in_dtype, void* out, px_dtype out_dtype, float scale,
                            void* hip_stream);
+
+/* Host only: the number of kernel launches of the 128-bit path px_dense_average makes for these
+ * arguments (what a profile of the call shows, and what a per-launch figure divides by); the
+ * element-wise kernel for a ragged tail or unaligned buffers is not counted.  0 for an empty call. */
+int64_t px_dense_average_launches(int n_buffers, int64_t count, px_dtype in_dtype, px_dtype out_dtype);
 
 /*
  * The pull side of a partitioned sparse variable (Sec. 3.1: workers pull the rows their

@@ -71,8 +71,11 @@ template <> struct In<uint16_t> {
 
 // A workgroup owns 4 consecutive kilobyte-rows of 256 pieces (16 bytes each) of every buffer; a thread
 // owns one piece of each row.
-#ifndef PX_DENSE_CHUNK_MB
-#define PX_DENSE_CHUNK_MB 8     // output bytes per launch, in MiB (0: one launch for everything)
+#ifndef PX_DENSE_LAUNCH_PIECES
+#define PX_DENSE_LAUNCH_PIECES (1 << 19)    // pieces per launch (0: one launch for everything)
+#endif
+#ifndef PX_DENSE_LAUNCH_OUT_MB
+#define PX_DENSE_LAUNCH_OUT_MB 16           // most output bytes per launch, in MiB
 #endif
 
 // The buffer pointers come from the context's device table (words) or, for up to PX_UPLOAD_WORDS
@@ -164,20 +167,31 @@ __global__ __launch_bounds__(256) void k_dense_scalar(const uint64_t* __restrict
     else ((float*) out)[i] = o;
 }
 
+// Pieces (16 bytes of every input buffer) one launch covers.  A long output is produced by several
+// launches in a row, each small enough for its output to stay in the L2 caches until the launch
+// ends and is written back in one burst: a steady trickle of writes between the reads costs this
+// machine more than the extra launches do.
+//   - 2^19 pieces (two workgroups of 1,024 pieces per compute unit): the measured optimum for 48 buffers;
+//   - more when there are few buffers, so that a launch still reads about 256 MiB;
+//   - never more than 16 MiB of output, half of what the L2 caches hold together.
+int64_t pieces_per_launch(int n_buffers, int64_t out_piece_bytes) {
+    if (PX_DENSE_LAUNCH_PIECES <= 0) return (int64_t) 1 << 62;         // one launch for everything
+    int64_t per = PX_DENSE_LAUNCH_PIECES;
+    const int64_t for_bytes = ((int64_t) 256 << 20) / ((int64_t) (n_buffers > 0 ? n_buffers : 1) * 16);
+    if (per < for_bytes) per = for_bytes;
+    const int64_t cap = ((int64_t) PX_DENSE_LAUNCH_OUT_MB << 20) / out_piece_bytes;
+    if (per > cap) per = cap;
+    return per;
+}
+
 template <typename TIN, bool OUT_BF16, bool CARRIED>
 void launch(px_ctx* ctx, const px_word_pack& pack, int n, int64_t count, bool vec, void* out, float scale,
             hipStream_t stream) {
     enum { E = In<TIN>::E };
     int64_t done = 0;
     if (vec) {
-        // A long output is produced by several launches in a row, each small enough for its output
-        // to stay in the L2 caches until the launch ends and is written back in one burst: a steady
-        // trickle of writes between the reads costs this machine more than the extra launches do.
         const int64_t pieces = count / E;
-        const int64_t out_piece_bytes = E * (OUT_BF16 ? 2 : 4);
-        int64_t per_launch = pieces;
-        if (PX_DENSE_CHUNK_MB > 0 && pieces * out_piece_bytes > ((int64_t) PX_DENSE_CHUNK_MB << 20))
-            per_launch = ((int64_t) PX_DENSE_CHUNK_MB << 20) / out_piece_bytes;     // measured: 8 MiB best of 4..16
+        const int64_t per_launch = pieces_per_launch(n, E * (OUT_BF16 ? 2 : 4));
         for (int64_t first = 0; first < pieces; first += per_launch) {
             const int64_t last = first + per_launch < pieces ? first + per_launch : pieces;
             k_dense_vec<TIN, OUT_BF16, CARRIED><<<px_round_up_8((unsigned) ((last - first + 256 * PX_DENSE_PIECES - 1) / (256 * PX_DENSE_PIECES))), 256, 0, stream>>>(
@@ -203,6 +217,15 @@ void launch_dtype(px_ctx* ctx, const px_word_pack& pack, int n, int64_t count, b
 }
 
 }  // namespace
+
+extern "C" int64_t px_dense_average_launches(int n_buffers, int64_t count, px_dtype in_dtype, px_dtype out_dtype) {
+    if (n_buffers < 1 || count < 1) return 0;
+    const int64_t e = in_dtype == PX_F32 ? 4 : 8;
+    const int64_t pieces = count / e;
+    if (pieces == 0) return 0;
+    const int64_t per = pieces_per_launch(n_buffers, e * (out_dtype == PX_F32 ? 4 : 2));
+    return (pieces + per - 1) / per;
+}
 
 extern "C" px_status px_dense_average(px_ctx* ctx, int n_buffers, const void* const* bufs, int64_t count,
                                       px_dtype in_dtype, void* out, px_dtype out_dtype, float scale,

@@ -36,6 +36,7 @@ EXPORTS = [
     "px_partition_rows", "px_sparse_apply_sgd", "px_sparse_apply_adagrad", "px_dense_average",
     "px_sparse_coalesce_apply_sgd", "px_sparse_coalesce_apply_adagrad", "px_sparse_lookup",
     "px_partition_cost_fit", "px_partition_cost_argmin", "px_partition_search_next",
+    "px_dense_average_launches",
 ]
 
 if not os.path.exists(LIBRARY):
@@ -84,6 +85,8 @@ lib.px_sparse_apply_adagrad.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp
                                         _f32, _vp]
 lib.px_dense_average.restype = _int
 lib.px_dense_average.argtypes = [_vp, _int, _pp, _i64, _int, _vp, _int, _f32, _vp]
+lib.px_dense_average_launches.restype = _i64
+lib.px_dense_average_launches.argtypes = [_int, _i64, _int, _int]
 
 
 _dp = ctypes.POINTER(ctypes.c_double)
@@ -265,6 +268,12 @@ class Context:
         assert out.is_contiguous() and out.numel() >= count
         self._check(lib.px_dense_average(self._h, n, _ptr_array(bufs), count, code, _ptr(out),
                                          _dtype_code(out), scale, _stream(stream)))
+
+
+def px_dense_average_launches(n_buffers: int, count: int, in_bf16: bool, out_bf16: bool = False) -> int:
+    """Kernel launches of the 128-bit path one px_dense_average call makes (host arithmetic)."""
+    return int(lib.px_dense_average_launches(n_buffers, count, PX_BF16 if in_bf16 else PX_F32,
+                                             PX_BF16 if out_bf16 else PX_F32))
 
 
 def _doubles(values):
