@@ -4,7 +4,7 @@
 // concatenated and values carrying the same index are accumulated.  On the GPU:
 //   1. pack    every input row becomes one 64-bit word  id << 32 | worker << LB | local row
 //   2. sort    stable least-significant-digit radix sort of the words on the id bits only
-//              (ceil(log2 vocab) bits, 8 per pass); value rows never move
+//              (ceil(log2 vocab) bits, 8 to 11 per pass); value rows never move
 //   3. heads   a row is a run head if its id differs from its predecessor's; counting and
 //              ranking the heads yields U, the distinct ids and every run's start.  Every sorted
 //              word is also turned into a row reference: the address of its value row, with
@@ -39,6 +39,9 @@ namespace {
 #endif
 #ifndef PX_TILE_TARGET
 #define PX_TILE_TARGET 8192     // grow the window until there are at most this many tiles
+#endif
+#ifndef PX_WIDE_DIGIT_BLOCKS
+#define PX_WIDE_DIGIT_BLOCKS 128   // sorts of up to this many blocks (256K rows) use digits of up to 11 bits
 #endif
 #ifndef PX_ALIGN_DIV
 #define PX_ALIGN_DIV 4          // a tile moves to a head only within the first 1/PX_ALIGN_DIV of its window
@@ -99,8 +102,8 @@ enum { SPAN_LONG_TILES = 32 };  // runs over more tiles than this get a whole wo
 struct Scratch {
     uint64_t* keys_a;
     uint64_t* keys_b;
-    uint32_t* hist;        // [PX_SORT_MAX_BLOCKS][256]
-    uint32_t* totals;      // [256] items per digit
+    uint32_t* hist;        // [PX_SORT_MAX_BLOCKS][bins], bins <= PX_RADIX_MAX
+    uint32_t* totals;      // [bins] items per digit
     uint32_t* hcount;      // heads per 2048-row block
     uint32_t* run_start;   // [M + 1]
     uint4* tile_info;      // [n_tiles] first row, flags, run index of the first row
@@ -127,8 +130,8 @@ inline Scratch carve(void* base, int64_t m, int64_t dim) {
     };
     s.keys_a = (uint64_t*) take((size_t) m * 8);
     s.keys_b = (uint64_t*) take((size_t) m * 8);
-    s.hist = (uint32_t*) take((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX * 4);
-    s.totals = (uint32_t*) take(PX_RADIX * 4);
+    s.hist = (uint32_t*) take((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX_MAX * 4);
+    s.totals = (uint32_t*) take(PX_RADIX_MAX * 4);
     s.hcount = (uint32_t*) take((n_hblocks + 1) * 4);
     s.run_start = (uint32_t*) take(((size_t) m + 1) * 4);
     s.tile_info = (uint4*) take((n_tiles + 1) * 16);
@@ -153,7 +156,7 @@ __device__ __forceinline__ uint32_t key_of(uint64_t w) { return (uint32_t) (w >>
 // device table (words) or, when they fit, inside the launch arguments (pack, CARRIED): then block 0
 // also stores them to the device table for the kernels that follow and clears the counters, and
 // the separate upload launch is saved.
-template <bool CARRIED>
+template <bool CARRIED, int BITS>
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__ words, px_word_pack pack,
                                                           uint32_t* __restrict__ counters, int n_counters,
                                                           int n_workers, int64_t m, int64_t vocab,
@@ -162,7 +165,8 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__
                                                           uint32_t* __restrict__ flags) {
     __shared__ uint32_t s_prefix[PX_MAX_SOURCES + 1];
     __shared__ uint64_t s_idx[CARRIED ? PX_UPLOAD_WORDS / 3 + 1 : 1];
-    __shared__ uint32_t s_hist[PX_RADIX];
+    enum { BINS = 1 << BITS };
+    __shared__ uint32_t s_hist[BINS];
     const int tid = threadIdx.x;
     if (CARRIED) {
         for (int i = tid; i <= n_workers; i += PX_SORT_THREADS) s_prefix[i] = (uint32_t) pack.w[2 * n_workers + i];
@@ -174,7 +178,7 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__
     } else {
         for (int i = tid; i <= n_workers; i += PX_SORT_THREADS) s_prefix[i] = (uint32_t) words[2 * n_workers + i];
     }
-    s_hist[tid] = 0u;
+    for (int b = tid; b < BINS; b += PX_SORT_THREADS) s_hist[b] = 0u;
     __syncthreads();
     const int64_t begin = (int64_t) blockIdx.x * chunk;
     int64_t end = begin + chunk;
@@ -212,12 +216,12 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__
                     v = 0;
                 }
                 keys[p] = ((uint64_t) (uint32_t) v << 32) | (uint64_t) (((uint32_t) src[j] << local_bits) | local[j]);
-                atomicAdd(&s_hist[(uint32_t) v & 255u], 1u);
+                atomicAdd(&s_hist[(uint32_t) v & (uint32_t) (BINS - 1)], 1u);
             }
         }
     }
     __syncthreads();
-    hist[(size_t) blockIdx.x * PX_RADIX + tid] = s_hist[tid];
+    for (int b = tid; b < BINS; b += PX_SORT_THREADS) hist[(size_t) blockIdx.x * BINS + b] = s_hist[b];
 }
 
 struct SortWords {
@@ -226,9 +230,10 @@ struct SortWords {
     uint64_t* out;
     int64_t n;
     int shift;                                      // bit offset inside the id
+    uint32_t mask;                                  // 2^digit width - 1
     __device__ int64_t count() const { return n; }
     __device__ Item load(int64_t i) const { return in[i]; }
-    __device__ uint32_t digit(Item v, int64_t) const { return (uint32_t) (v >> (32 + shift)) & 255u; }
+    __device__ uint32_t digit(Item v, int64_t) const { return (uint32_t) (v >> (32 + shift)) & mask; }
     __device__ void note(int64_t, uint32_t) const {}
     __device__ void store(uint32_t dst, Item v) const { out[dst] = v; }
     __device__ void publish(int, uint32_t, uint32_t) const {}
@@ -1086,36 +1091,59 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
     }
     host_words[3 * n_workers] = (uint64_t) run;
     const px_sort_geom g = px_sort_geometry(m);
-    if (3 * n_workers + 1 <= PX_UPLOAD_WORDS) {
-        // up to 85 workers: the tables ride in the pack kernel's own arguments
-        px_word_pack pack;
-        memcpy(pack.w, host_words, (size_t) (3 * n_workers + 1) * sizeof(uint64_t));
-        k_pack<true><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, pack, sc.counters, 64, n_workers, m, vocab,
-                                                                 local_bits, sc.keys_a, sc.hist, g.chunk, ctx->d_flags);
-    } else {
-        px_status st = px_upload_words(ctx, ctx->d_words, host_words, 3 * n_workers + 1, sc.counters, 64, stream);
-        if (st != PX_OK) return st;
-        px_word_pack unused;
-        unused.w[0] = 0;
-        k_pack<false><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, unused, sc.counters, 64, n_workers, m, vocab,
-                                                                  local_bits, sc.keys_a, sc.hist, g.chunk, ctx->d_flags);
-    }
-    int key_bits = bits_for((uint64_t) (vocab - 1));
-    int passes = (key_bits + 7) / 8;
+    // Digits of up to PX_RADIX_MAX_BITS bits: as few passes as that allows, all of the same width
+    // (at least 8 bits).
+    // Wide digits only while a pass is bound by its launches (few blocks): at 512 blocks the 2,048-bin
+    // histogram matrix makes a pass cost twice an 8-bit one.
+    const int key_bits = bits_for((uint64_t) (vocab - 1));
+    const int widest = g.n_blocks <= PX_WIDE_DIGIT_BLOCKS ? PX_RADIX_MAX_BITS : 8;
+    int passes = (key_bits + widest - 1) / widest;
     if (passes < 1) passes = 1;
-    uint64_t* src = sc.keys_a;
-    uint64_t* dst = sc.keys_b;
-    for (int p = 0; p < passes; ++p) {
-        SortWords pol{src, dst, m, 8 * p};
-        if (p > 0) pxr::k_radix_hist<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, g.chunk);
-        const int own = g.n_blocks <= PX_OWN_PREFIX_BLOCKS ? g.n_blocks : 0;
-        if (!own) pxr::k_radix_prefix<<<PX_RADIX / 4, 256, 0, stream>>>(sc.hist, g.n_blocks, sc.totals);
-        pxr::k_radix_scatter<SortWords><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, sc.totals, g.chunk, own);
-        uint64_t* t = src;
-        src = dst;
-        dst = t;
-    }
-    const uint64_t* sorted = src;
+    int digit_bits = (key_bits + passes - 1) / passes;
+    if (digit_bits < 8) digit_bits = 8;
+    uint64_t* sorted_words = nullptr;
+    uint64_t* other_words = nullptr;
+    px_status sort_status = PX_OK;
+    auto sort = [&](auto bits_tag) {
+        constexpr int BITS = decltype(bits_tag)::value;
+        if (3 * n_workers + 1 <= PX_UPLOAD_WORDS) {
+            // up to 85 workers: the tables ride in the pack kernel's own arguments
+            px_word_pack pack;
+            memcpy(pack.w, host_words, (size_t) (3 * n_workers + 1) * sizeof(uint64_t));
+            k_pack<true, BITS><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, pack, sc.counters, 64, n_workers, m,
+                                                                           vocab, local_bits, sc.keys_a, sc.hist, g.chunk,
+                                                                           ctx->d_flags);
+        } else {
+            sort_status = px_upload_words(ctx, ctx->d_words, host_words, 3 * n_workers + 1, sc.counters, 64, stream);
+            if (sort_status != PX_OK) return;
+            px_word_pack unused;
+            unused.w[0] = 0;
+            k_pack<false, BITS><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, unused, sc.counters, 64, n_workers, m,
+                                                                            vocab, local_bits, sc.keys_a, sc.hist, g.chunk,
+                                                                            ctx->d_flags);
+        }
+        uint64_t* src = sc.keys_a;
+        uint64_t* dst = sc.keys_b;
+        for (int p = 0; p < passes; ++p) {
+            SortWords pol{src, dst, m, BITS * p, (uint32_t) ((1 << BITS) - 1)};
+            if (p > 0) pxr::k_radix_hist<SortWords, BITS><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, g.chunk);
+            const int own = g.n_blocks <= PX_OWN_PREFIX_BLOCKS ? g.n_blocks : 0;
+            if (!own) pxr::k_radix_prefix<<<(1 << BITS) / 4, 256, 0, stream>>>(sc.hist, g.n_blocks, 1 << BITS, sc.totals);
+            pxr::k_radix_scatter<SortWords, BITS><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, sc.totals, g.chunk, own);
+            uint64_t* t = src;
+            src = dst;
+            dst = t;
+        }
+        sorted_words = src;
+        other_words = dst;
+    };
+    if (digit_bits <= 8) sort(std::integral_constant<int, 8>());
+    else if (digit_bits == 9) sort(std::integral_constant<int, 9>());
+    else if (digit_bits == 10) sort(std::integral_constant<int, 10>());
+    else sort(std::integral_constant<int, 11>());
+    if (sort_status != PX_OK) return sort_status;
+    uint64_t* dst = other_words;
+    const uint64_t* sorted = sorted_words;
 
     const int tile_rows = tile_rows_for(m);
     const int64_t n_tiles = (m + tile_rows - 1) / tile_rows;

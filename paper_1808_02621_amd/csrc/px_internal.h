@@ -45,7 +45,8 @@ enum {
     PX_SORT_ITEMS = 8,
     PX_SORT_TILE = PX_SORT_THREADS * PX_SORT_ITEMS,   // items ranked at once in LDS
     PX_SORT_MAX_BLOCKS = 512,     // multiple of 64
-    PX_RADIX = 256
+    PX_RADIX_MAX_BITS = 11,       // widest digit of a counting pass
+    PX_RADIX_MAX = 1 << PX_RADIX_MAX_BITS
 };
 #ifndef PX_OWN_PREFIX_BLOCKS
 #define PX_OWN_PREFIX_BLOCKS 32   // up to this many blocks a scatter block sums the histogram rows itself

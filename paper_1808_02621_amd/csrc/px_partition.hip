@@ -50,7 +50,7 @@ struct ShardPass {
 
 extern "C" size_t px_partition_scratch_bytes(int64_t cap) {
     if (cap < 0) return 0;
-    return px_align_up((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX * 4, 256) + px_align_up(PX_RADIX * 4, 256);
+    return px_align_up((size_t) PX_SORT_MAX_BLOCKS * 256 * 4, 256) + px_align_up(256 * 4, 256);
 }
 
 extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids,
@@ -70,12 +70,12 @@ extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const in
     if (scratch_bytes < need) return px_fail(ctx, PX_ERR_SCRATCH_TOO_SMALL, "scratch %zu < %zu bytes", scratch_bytes, need);
 
     uint32_t* hist = (uint32_t*) scratch;
-    uint32_t* totals = (uint32_t*) ((char*) scratch + px_align_up((size_t) PX_SORT_MAX_BLOCKS * PX_RADIX * 4, 256));
+    uint32_t* totals = (uint32_t*) ((char*) scratch + px_align_up((size_t) PX_SORT_MAX_BLOCKS * 256 * 4, 256));
     const px_sort_geom g = px_sort_geometry(cap);
     ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard, out_offsets};
-    pxr::k_radix_hist<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.chunk);
+    pxr::k_radix_hist<ShardPass, 8><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.chunk);
     const int own = g.n_blocks <= PX_OWN_PREFIX_BLOCKS ? g.n_blocks : 0;
-    if (!own) pxr::k_radix_prefix<<<PX_RADIX / 4, 256, 0, stream>>>(hist, g.n_blocks, totals);
-    pxr::k_radix_scatter<ShardPass><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, totals, g.chunk, own);
+    if (!own) pxr::k_radix_prefix<<<256 / 4, 256, 0, stream>>>(hist, g.n_blocks, 256, totals);
+    pxr::k_radix_scatter<ShardPass, 8><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, totals, g.chunk, own);
     return px_check_hip(ctx, hipGetLastError(), "partition launch");
 }

@@ -1,11 +1,11 @@
-// Stable 8-bit counting pass for wave64: the building block of the id sort
+// Stable counting pass (8- to 11-bit digits) for wave64: the building block of the id sort
 // (least-significant-digit radix sort) and of the shard partition.
 //
 // A pass is three kernels and uses no atomics on global memory and no waiting
 // between workgroups:
-//   hist     block b counts the digits of its chunk        -> hist[b][256]
+//   hist     block b counts the digits of its chunk        -> hist[b][bins]
 //   prefix   one wave per digit turns its column of hist into an exclusive prefix
-//            over the blocks and writes the digit's total  -> hist[b][256], totals[256]
+//            over the blocks and writes the digit's total  -> hist[b][bins], totals[bins]
 //   scatter  block b scans the totals, adds its own prefix row, then ranks its
 //            chunk tile by tile in LDS and writes every item to its final place.
 // With at most PX_OWN_PREFIX_BLOCKS blocks the prefix kernel is skipped: every scatter block
@@ -56,16 +56,21 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
     return base + incl - v;
 }
 
-// Policy P supplies: typedef Item; count(); load(i); digit(item, i); note(i, d); store(dst, item);
-// publish(bin, start, grand): called once per bin by block 0 of the scatter with the bin's first
-// output position and the item count.
+// Policy P supplies: typedef Item; count(); load(i); digit(item, i) < 2^BITS; note(i, d);
+// store(dst, item); publish(bin, start, grand): called once per bin by block 0 of the scatter
+// with the bin's first output position and the item count.
+//
+// BITS is the digit width, 8 ... 11: 2^BITS bins, each thread of a block owns 2^BITS / 256
+// consecutive bins.  Wider digits cost more LDS and a longer ranking loop per pass and save whole
+// passes: ids of 17 to 22 bits sort in two passes instead of three.
 
-template <class P>
+template <class P, int BITS>
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_hist(P p, uint32_t* __restrict__ hist,
                                                                 int64_t chunk) {
-    __shared__ uint32_t s_hist[PX_RADIX];
+    enum { BINS = 1 << BITS };
+    __shared__ uint32_t s_hist[BINS];
     const int tid = threadIdx.x;
-    s_hist[tid] = 0u;
+    for (int b = tid; b < BINS; b += PX_SORT_THREADS) s_hist[b] = 0u;
     __syncthreads();
     const int64_t n = p.count();
     const int64_t begin = (int64_t) blockIdx.x * chunk;
@@ -90,12 +95,12 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_hist(P p, uint32_t* _
         }
     }
     __syncthreads();
-    hist[(size_t) blockIdx.x * PX_RADIX + tid] = s_hist[tid];
+    for (int b = tid; b < BINS; b += PX_SORT_THREADS) hist[(size_t) blockIdx.x * BINS + b] = s_hist[b];
 }
 
 // hist[b][bin] <- sum of hist[b'][bin] over b' < b;  totals[bin] <- sum over all blocks.
-// Grid: PX_RADIX / 4 blocks of 256 threads, one wave per bin; lane l owns blocks [l*per, (l+1)*per).
-static __global__ __launch_bounds__(256) void k_radix_prefix(uint32_t* __restrict__ hist, int n_blocks,
+// Grid: bins / 4 blocks of 256 threads, one wave per bin; lane l owns blocks [l*per, (l+1)*per).
+static __global__ __launch_bounds__(256) void k_radix_prefix(uint32_t* __restrict__ hist, int n_blocks, int bins,
                                                       uint32_t* __restrict__ totals) {
     enum { PER = (PX_SORT_MAX_BLOCKS + 63) / 64 };
     const uint32_t lane = lane_id();
@@ -104,7 +109,7 @@ static __global__ __launch_bounds__(256) void k_radix_prefix(uint32_t* __restric
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
         const int b = (int) lane * PER + j;
-        v[j] = b < n_blocks ? hist[(size_t) b * PX_RADIX + bin] : 0u;
+        v[j] = b < n_blocks ? hist[(size_t) b * bins + bin] : 0u;
     }
     uint32_t sum = 0;
 #pragma unroll
@@ -114,23 +119,24 @@ static __global__ __launch_bounds__(256) void k_radix_prefix(uint32_t* __restric
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
         const int b = (int) lane * PER + j;
-        if (b < n_blocks) hist[(size_t) b * PX_RADIX + bin] = run;
+        if (b < n_blocks) hist[(size_t) b * bins + bin] = run;
         run += v[j];
     }
     if (lane == 63) totals[bin] = incl;
 }
 
 // own_prefix_blocks > 0: hist holds the raw counts of that many blocks and totals is not read.
-template <class P>
+template <class P, int BITS>
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const uint32_t* __restrict__ hist,
                                                                    const uint32_t* __restrict__ totals,
                                                                    int64_t chunk, int own_prefix_blocks) {
     typedef typename P::Item Item;
+    enum { BINS = 1 << BITS, BPT = BINS / PX_SORT_THREADS };      // bins per thread: tid*BPT .. tid*BPT + BPT - 1
     __shared__ Item s_items[PX_SORT_TILE];
-    __shared__ uint8_t s_dig[PX_SORT_TILE];
-    __shared__ uint32_t s_wcnt[4][PX_RADIX];
-    __shared__ uint32_t s_binstart[PX_RADIX];
-    __shared__ uint32_t s_gdst[PX_RADIX];
+    __shared__ uint16_t s_dig[PX_SORT_TILE];
+    __shared__ uint32_t s_wcnt[4][BINS];
+    __shared__ uint32_t s_binstart[BINS];
+    __shared__ uint32_t s_gdst[BINS];
     __shared__ uint32_t s_wave[4];
 
     const int tid = threadIdx.x;
@@ -138,24 +144,39 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
     const int wave = tid >> 6;
     const uint64_t below = lanes_below();
 
-    // Where bin `tid` of this block starts in the output.
-    uint32_t grand, bin_total, before;
-    if (own_prefix_blocks > 0) {
-        bin_total = 0u;
-        before = 0u;
+    // Where this thread's bins start in the output, for this block.
+    uint32_t gpos[BPT];
+    {
+        uint32_t bin_total[BPT], before[BPT];
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            const int bin = tid * BPT + k;
+            if (own_prefix_blocks > 0) {
+                bin_total[k] = 0u;
+                before[k] = 0u;
 #pragma unroll 8
-        for (int b = 0; b < own_prefix_blocks; ++b) {
-            const uint32_t c = hist[(size_t) b * PX_RADIX + tid];
-            bin_total += c;
-            before += b < (int) blockIdx.x ? c : 0u;
+                for (int b = 0; b < own_prefix_blocks; ++b) {
+                    const uint32_t c = hist[(size_t) b * BINS + bin];
+                    bin_total[k] += c;
+                    before[k] += b < (int) blockIdx.x ? c : 0u;
+                }
+            } else {
+                bin_total[k] = totals[bin];
+                before[k] = hist[(size_t) blockIdx.x * BINS + bin];
+            }
         }
-    } else {
-        bin_total = totals[tid];
-        before = hist[(size_t) blockIdx.x * PX_RADIX + tid];
+        uint32_t mine = 0;
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) mine += bin_total[k];
+        uint32_t grand;
+        uint32_t start = block_exclusive_scan_256(mine, s_wave, &grand);
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            gpos[k] = start + before[k];
+            if (blockIdx.x == 0) p.publish(tid * BPT + k, start, grand);
+            start += bin_total[k];
+        }
     }
-    const uint32_t bin_start = block_exclusive_scan_256(bin_total, s_wave, &grand);
-    uint32_t gpos = bin_start + before;
-    if (blockIdx.x == 0) p.publish(tid, bin_start, grand);
 
     const int64_t n = p.count();
     const int64_t begin = (int64_t) blockIdx.x * chunk;
@@ -165,7 +186,9 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
     for (int64_t tile0 = begin; tile0 < end; tile0 += PX_SORT_TILE) {
         const int tcount = (int) ((end - tile0) < PX_SORT_TILE ? (end - tile0) : PX_SORT_TILE);
 #pragma unroll
-        for (int w = 0; w < 4; ++w) s_wcnt[w][tid] = 0u;
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int k = 0; k < BPT; ++k) s_wcnt[w][tid * BPT + k] = 0u;
         __syncthreads();
 
         Item it[PX_SORT_ITEMS];
@@ -182,7 +205,7 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
             }
             uint64_t same = __ballot(valid);
 #pragma unroll
-            for (int bit = 0; bit < 8; ++bit) {
+            for (int bit = 0; bit < BITS; ++bit) {
                 const bool one = (d >> bit) & 1u;
                 const uint64_t bb = __ballot(one);
                 same &= one ? bb : ~bb;
@@ -202,17 +225,29 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
         __syncthreads();
 
         // Per bin: exclusive prefix over the four waves, then over the bins.
-        const uint32_t c0 = s_wcnt[0][tid], c1 = s_wcnt[1][tid], c2 = s_wcnt[2][tid], c3 = s_wcnt[3][tid];
-        s_wcnt[0][tid] = 0u;
-        s_wcnt[1][tid] = c0;
-        s_wcnt[2][tid] = c0 + c1;
-        s_wcnt[3][tid] = c0 + c1 + c2;
-        const uint32_t tot = c0 + c1 + c2 + c3;
+        uint32_t tot[BPT];
+        uint32_t mine = 0;
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            const int bin = tid * BPT + k;
+            const uint32_t c0 = s_wcnt[0][bin], c1 = s_wcnt[1][bin], c2 = s_wcnt[2][bin], c3 = s_wcnt[3][bin];
+            s_wcnt[0][bin] = 0u;
+            s_wcnt[1][bin] = c0;
+            s_wcnt[2][bin] = c0 + c1;
+            s_wcnt[3][bin] = c0 + c1 + c2;
+            tot[k] = c0 + c1 + c2 + c3;
+            mine += tot[k];
+        }
         uint32_t tile_total;
-        const uint32_t bs = block_exclusive_scan_256(tot, s_wave, &tile_total);
-        s_binstart[tid] = bs;
-        s_gdst[tid] = gpos - bs;                   // wraps; the sum below is exact mod 2^32
-        gpos += tot;
+        uint32_t bs = block_exclusive_scan_256(mine, s_wave, &tile_total);
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            const int bin = tid * BPT + k;
+            s_binstart[bin] = bs;
+            s_gdst[bin] = gpos[k] - bs;            // wraps; the sum below is exact mod 2^32
+            gpos[k] += tot[k];
+            bs += tot[k];
+        }
         __syncthreads();
 
 #pragma unroll
@@ -221,7 +256,7 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
             if (local < tcount) {
                 const uint32_t pos = s_binstart[dg[i]] + s_wcnt[wave][dg[i]] + rk[i];
                 s_items[pos] = it[i];
-                s_dig[pos] = (uint8_t) dg[i];
+                s_dig[pos] = (uint16_t) dg[i];
             }
         }
         __syncthreads();
