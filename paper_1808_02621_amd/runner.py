@@ -69,7 +69,10 @@ def coalesce(ctx: px.Context, b: SparseBuffers, scale: float = 1.0, stream=None)
 
 
 def partition(ctx: px.Context, b: SparseBuffers, stream=None) -> None:
-    ctx.px_partition_rows(b.out_ids, b.out_num, b.total_rows, b.n_shards, b.hash, b.shard, b.perm,
+    # there are no more distinct ids than input rows, nor than rows in the table: the tighter bound
+    # sizes the partition's launches
+    cap = max(1, min(b.total_rows, b.vocab))
+    ctx.px_partition_rows(b.out_ids, b.out_num, cap, b.n_shards, b.hash, b.shard, b.perm,
                           b.offsets, b.part_scratch, stream)
 
 
