@@ -687,6 +687,26 @@ def test_dense_average(gpu, n_buffers, count, bf16):
         assert np.array_equal(out.cpu().numpy(), bufs[0])
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_dense_average_over_several_launches_with_a_ragged_tail(gpu, bf16):
+    """Two buffers: a launch covers 16 MiB of output, so this count takes two launches (the second one
+    partly filled, its last workgroup ragged) plus the element-wise tail; integer values, bit-exact."""
+    ctx, px, runner = gpu
+    count = 6_300_003
+    assert px.px_dense_average_launches(2, count, bf16) == 2
+    rng = np.random.default_rng(5 + int(bf16))
+    bufs = [inputs.small_integer_values(rng, count) for _ in range(2)]
+    if bf16:
+        bufs = [inputs.f32_to_bf16_bits(b) for b in bufs]
+    d = [runner.to_device(b) for b in bufs]
+    out = torch.full((count + 8,), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.px_dense_average(d, count, out, 1.0)
+    assert np.array_equal(out[:count].cpu().numpy(), oracle.dense_average(bufs, average=False))
+    assert bool(torch.isnan(out[count:]).all())                        # nothing written past the end
+    ctx.px_dense_average(d, count, out, 0.5)
+    assert np.array_equal(out[:count].cpu().numpy(), oracle.dense_average(bufs, average=True))
+
+
 def test_dense_average_bf16_output_and_unaligned(gpu):
     ctx, px, runner = gpu
     rng = np.random.default_rng(21)
