@@ -57,3 +57,17 @@ def test_host_only_calls(library):
     library.px_partition_scratch_bytes.restype = ctypes.c_size_t
     library.px_partition_scratch_bytes.argtypes = [ctypes.c_int64]
     assert library.px_partition_scratch_bytes(1000) > 0
+
+
+def test_dense_launch_count_is_host_arithmetic(library):
+    """2^19 16-byte pieces per launch, more for few buffers, at most 16 MiB of output."""
+    f = library.px_dense_average_launches
+    f.restype = ctypes.c_int64
+    f.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int]
+    F32, BF16 = 0, 1
+    assert f(48, 1 << 26, BF16, F32) == 16          # the headline workload: 2^23 pieces
+    assert f(48, 1 << 23, F32, F32) == 4            # 2^21 pieces
+    assert f(8, 1 << 22, F32, F32) == 1             # few buffers: one launch of 16 MiB of output
+    assert f(2, 6_300_003, F32, F32) == 2 and f(2, 6_300_003, BF16, F32) == 2
+    assert f(4, 65_536, F32, F32) == 1
+    assert f(4, 3, F32, F32) == 0 and f(0, 100, F32, F32) == 0 and f(4, 0, F32, F32) == 0
