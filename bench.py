@@ -505,7 +505,8 @@ def main():
     dw.pull_setup()
     pull_avg, pull_min = event_timed(torch, dw.pull, max(5, args.steps // 2), 2)
     result["pull_side"] = {
-        "what": "px_sparse_lookup: rows of every worker's ids gathered in batch order, all tables",
+        "what": "px_sparse_lookup: rows of every worker's ids gathered in batch order, all tables; the bytes count "
+                "every requested row's read, repeated ids included, so cache hits can lift the figure above HBM's",
         "avg_us": pull_avg * 1e6, "algorithmic_bytes": dw.pull_bytes(),
         "achieved_gbps": dw.pull_bytes() / pull_avg / 1e9, "frac": dw.pull_bytes() / pull_avg / 1e9 / HBM_PEAK_GBPS,
     }

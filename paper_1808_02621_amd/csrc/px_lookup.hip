@@ -71,7 +71,21 @@ __global__ __launch_bounds__(256) void k_lookup(LookupArgs p) {
                 if (ok[r]) v[r] = ((const V*) (p.table + (size_t) id[r] * p.dim))[p0];
 #pragma unroll
             for (int r = 0; r < R; ++r)
-                if (ok[r]) ((V*) (p.out + (size_t) k[r] * p.dim))[p0] = v[r];
+                if (ok[r]) {
+#ifndef PX_LOOKUP_PLAIN_STORE
+                    // the gathered rows are written once and not read here again: storing them past the
+                    // caches leaves the L2 to the table rows, which hot ids make it re-read
+                    if constexpr (VEC) {
+                        typedef float v4f __attribute__((ext_vector_type(4)));
+                        v4f t = {v[r].x, v[r].y, v[r].z, v[r].w};
+                        __builtin_nontemporal_store(t, (v4f*) (p.out + (size_t) k[r] * p.dim) + p0);
+                    } else {
+                        ((V*) (p.out + (size_t) k[r] * p.dim))[p0] = v[r];
+                    }
+#else
+                    ((V*) (p.out + (size_t) k[r] * p.dim))[p0] = v[r];
+#endif
+                }
         }
     }
 }
