@@ -700,10 +700,13 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
             load_state(tc, kc, wsc, asc);
         }
         for (int64_t r = from; r < to; r += B) {
+            // Loads come back in the order they were issued, so the references of batch k + 2 go out
+            // before the rows of batch k + 1: the next iteration then finds them without having to
+            // wait for those rows, and two batches of rows really are in flight.
+            load_refs(r + 2 * B, wf, kf);
             load_rows(wn, rn);
             tn = tails_of(r + B, wn);
             load_state(tn, kn, wsn, asn);
-            load_refs(r + 2 * B, wf, kf);
             if (r + B <= to) {
 #pragma unroll
                 for (int j = 0; j < B; ++j) {
