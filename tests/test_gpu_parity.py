@@ -707,6 +707,29 @@ def test_dense_average_over_several_launches_with_a_ragged_tail(gpu, bf16):
     assert np.array_equal(out[:count].cpu().numpy(), oracle.dense_average(bufs, average=True))
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_dense_average_random_cases(gpu, seed):
+    """Random buffer counts, lengths, element types, output types and alignments; nothing written past the end."""
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(9000 + seed)
+    n = int(rng.choice([1, 2, 3, 5, 8, 17, 48, 64, 90]))
+    count = int(rng.choice([1, 7, 255, 1024, 4097, 65_537, 300_001, 1_048_576 + 13, 2_500_000]))
+    count = min(count, 30_000_000 // n)
+    bf16 = bool(rng.integers(0, 2))
+    out_bf16 = bool(rng.integers(0, 4) == 0)
+    off = int(rng.choice([0, 0, 0, 1, 4]))                        # elements into the allocation: alignment
+    bufs = [rng.standard_normal(count + off, dtype=np.float32) for _ in range(n)]
+    if bf16:
+        bufs = [inputs.f32_to_bf16_bits(b) for b in bufs]
+    d = [runner.to_device(b)[off:] for b in bufs]
+    out = torch.full((count + 4,), 7.0, dtype=torch.bfloat16 if out_bf16 else torch.float32, device="cuda")
+    scale = float(rng.choice([1.0, 1.0 / n]))
+    ctx.px_dense_average(d, count, out, scale)
+    ref = oracle.dense_average([b[off:] for b in bufs], average=(scale != 1.0))
+    close(out[:count].float().cpu().numpy(), ref, 1e-2 if out_bf16 else REL_TOL)
+    assert bool((out[count:].float() == 7.0).all())
+
+
 def test_dense_average_bf16_output_and_unaligned(gpu):
     ctx, px, runner = gpu
     rng = np.random.default_rng(21)
