@@ -30,11 +30,19 @@ struct LookupArgs {
     int pieces;
 };
 
+#ifndef PX_LOOKUP_WIDE_ROWS
+#define PX_LOOKUP_WIDE_ROWS 1
+#endif
+#ifndef PX_LOOKUP_WIDE_DIE
+#define PX_LOOKUP_WIDE_DIE true
+#endif
 #ifndef PX_LOOKUP_BLOCKS
 #define PX_LOOKUP_BLOCKS 65536    // most workgroups of one lookup launch (measured: 2,048 ... 16,384 are 2-7 % slower)
 #endif
 
-template <bool VEC, int G, int R>
+// DIE: the hardware's workgroup number is mapped so that each of the 8 dies gathers one contiguous
+// eighth of the requested rows (the grid is then a multiple of 8).
+template <bool VEC, int G, int R, bool DIE>
 __global__ __launch_bounds__(256) void k_lookup(LookupArgs p) {
     typedef typename std::conditional<VEC, float4, float>::type V;
     enum { E = VEC ? 4 : 1 };
@@ -49,7 +57,7 @@ __global__ __launch_bounds__(256) void k_lookup(LookupArgs p) {
         if (last > n) last = n;
     }
     const int gl = threadIdx.x % G;
-    const int64_t group = (int64_t) blockIdx.x * (256 / G) + threadIdx.x / G;
+    const int64_t group = (int64_t) (DIE ? px_die_contiguous_block(blockIdx.x, gridDim.x) : blockIdx.x) * (256 / G) + threadIdx.x / G;
     const int64_t n_groups = (int64_t) gridDim.x * (256 / G);
     for (int64_t j0 = first + group * R; j0 < last; j0 += n_groups * R) {
         int64_t k[R], id[R];
@@ -100,11 +108,13 @@ void launch(const LookupArgs& p, hipStream_t stream) {
         int64_t b = (p.cap + (256 / g) * r - 1) / ((256 / g) * r);
         if (b > PX_LOOKUP_BLOCKS) b = PX_LOOKUP_BLOCKS;
         if (b < 1) b = 1;
-        return dim3((unsigned) b, 1, 1);
+        return dim3(px_round_up_8((unsigned) b), 1, 1);
     };
-    if (p.pieces <= 16) k_lookup<VEC, 16, 4><<<blocks(16, 4), 256, 0, stream>>>(p);
-    else if (p.pieces <= 32) k_lookup<VEC, 32, 4><<<blocks(32, 4), 256, 0, stream>>>(p);
-    else k_lookup<VEC, 64, 2><<<blocks(64, 2), 256, 0, stream>>>(p);
+    // rows of more than 32 pieces (512 bytes): one row in flight per lane group and die-contiguous
+    // numbering (measured: NMT-like 147 -> 132 us, Large-vocab LM 56 -> 54.5 us; for narrower rows the numbering costs up to 9 %)
+    if (p.pieces <= 16) k_lookup<VEC, 16, 4, false><<<blocks(16, 4), 256, 0, stream>>>(p);
+    else if (p.pieces <= 32) k_lookup<VEC, 32, 4, false><<<blocks(32, 4), 256, 0, stream>>>(p);
+    else k_lookup<VEC, 64, PX_LOOKUP_WIDE_ROWS, PX_LOOKUP_WIDE_DIE><<<blocks(64, PX_LOOKUP_WIDE_ROWS), 256, 0, stream>>>(p);
 }
 
 }  // namespace
