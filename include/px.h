@@ -30,10 +30,13 @@
  *   - Host arrays (pointer tables, counts) are read before the call returns.
  *   - Argument errors are found on the host before anything is enqueued and
  *     leave all buffers untouched.  Errors that only the device can see (an id
- *     outside the table) raise a sticky flag in the context: the kernels stay
- *     in bounds, the coalesced count becomes 0, and every later apply call on
- *     that context leaves the table untouched until px_device_status has
- *     reported and cleared the flag.
+ *     outside the table; an update handed a repeated id) raise a sticky flag in
+ *     the context: the kernels stay in bounds, the coalesced count becomes 0
+ *     for a bad id, the offending rows are not updated, and every later update
+ *     on that context leaves its table untouched until px_device_status has
+ *     reported and cleared the flag.  A caller that never polls therefore
+ *     loses updates after the first error: poll once per step (it is the one
+ *     call that blocks) or at whatever interval losing updates is acceptable.
  *   - One context per stream; calls on one context must not overlap.
  *   - Empty inputs (no rows, a worker with no rows, count 0) are valid no-ops.
  */
@@ -54,7 +57,7 @@ typedef enum {
     PX_ERR_INVALID_ARG = 1,        /* bad pointer, size, dtype, alignment or unsupported shape */
     PX_ERR_INDEX_OUT_OF_RANGE = 2, /* an id outside [0, vocab) reached the device */
     PX_ERR_SCRATCH_TOO_SMALL = 3,
-    PX_ERR_NOT_UNIQUE = 4,         /* reserved: apply was handed a repeated id */
+    PX_ERR_NOT_UNIQUE = 4,         /* an update was handed the same id in adjacent positions */
     PX_ERR_DEVICE = 5              /* a HIP runtime call failed */
 } px_status;
 
@@ -79,7 +82,8 @@ const char* px_status_string(px_status s);
 const char* px_last_error(const px_ctx* ctx);
 
 /* Waits for `hip_stream`, then reports and clears the context's device-side
- * error flag: PX_OK or PX_ERR_INDEX_OUT_OF_RANGE.  The only call that blocks. */
+ * error flag: PX_OK, PX_ERR_INDEX_OUT_OF_RANGE, or PX_ERR_NOT_UNIQUE (in that
+ * order of precedence when both were raised).  The only call that blocks. */
 px_status px_device_status(px_ctx* ctx, void* hip_stream);
 
 /* Bytes of scratch px_sparse_coalesce needs for `total_rows` input rows (over
@@ -153,7 +157,13 @@ px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const int64_t* num_
  *   perm     dev int32[cap] from px_partition_rows, or NULL for the identity
  *   range    dev int64[2] = {first, last} positions of perm to apply (e.g. two
  *            consecutive entries of out_offsets: one shard), or NULL for all *num_ids
- * Precondition: the ids are distinct; rows and table do not overlap.
+ * Precondition: the ids are distinct; rows and table do not overlap.  Two lane groups
+ * updating one row would race, so every position whose id equals that of a neighbouring
+ * position (k - 1 or k + 1; in a sorted list, such as px_sparse_coalesce's output, every
+ * repeat is one) is skipped and raises the context's flag (PX_ERR_NOT_UNIQUE from
+ * px_device_status).  The other rows of that call are updated unless their workgroup started
+ * after the flag went up (a launch of one workgroup updates all of them).  Repeats that are
+ * not adjacent are not detected: the result for those rows is then undefined.
  */
 px_status px_sparse_apply_sgd(px_ctx* ctx, float* table, int64_t vocab, int64_t dim,
                               const int64_t* ids, const float* rows, const int64_t* num_ids,
@@ -163,8 +173,14 @@ px_status px_sparse_apply_sgd(px_ctx* ctx, float* table, int64_t vocab, int64_t 
 /*
  * Sparse variable update by Adagrad, element-wise on the touched rows:
  *   accum[id] += g*g ;  table[id] -= lr * g / (sqrt(accum[id]) + eps)   (updated accum)
+ * The paper's own example uses plain gradient descent (Fig. 4) and leaves the optimizer to the
+ * single-GPU graph it transforms (Sec. 4.1); what it fixes is where and when the update runs:
+ * once per touched row, from the aggregated gradient, on the partition that owns the row
+ * (Sec. 2.1, Sec. 4.3).  The rule itself is Adagrad as published (Duchi et al., 2011) in the
+ * form the sparse language-model workloads use: a per-element accumulator of the same shape as
+ * the variable, read after it has been increased by g*g, eps added outside the square root.
  * accum: dev float[vocab][dim], same layout as table, updated in place.
- * Other arguments as px_sparse_apply_sgd.
+ * Other arguments, the precondition and the error behaviour as px_sparse_apply_sgd.
  */
 px_status px_sparse_apply_adagrad(px_ctx* ctx, float* table, float* accum, int64_t vocab,
                                   int64_t dim, const int64_t* ids, const float* rows,

@@ -36,9 +36,14 @@ AGG_SUM, AGG_AVERAGE = 0, 1
 _lib = None
 
 
-def build(source: str = SOURCE, output: str = LIBRARY) -> str:
-    """Compile the oracle with g++ (always recompiles)."""
-    cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-Wall", "-Wextra",
+SANITIZE_FLAGS = ("-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                  "-fno-sanitize-recover=all")
+
+
+def build(source: str = SOURCE, output: str = LIBRARY, extra_flags: Sequence[str] = ()) -> str:
+    """Compile the oracle with g++ (always recompiles).  extra_flags, e.g. SANITIZE_FLAGS, come
+    after -O2 and so override it."""
+    cmd = ["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-Wall", "-Wextra", *extra_flags,
            "-o", output, source]
     subprocess.run(cmd, check=True)
     return output

@@ -82,7 +82,7 @@ template <bool ADAGRAD, bool VEC, int G, int C, int R>
 __global__ __launch_bounds__(256) void k_apply(ApplyArgs p) {
     typedef typename Piece<VEC>::V V;
     enum { E = Piece<VEC>::E };
-    if (p.flags[0] & PXF_BAD_ID) return;             // an earlier call saw a bad id: leave the table alone
+    if (p.flags[0]) return;                          // an earlier call saw a bad or repeated id: leave the table alone
     int64_t n = p.num_ids[0];
     if (n < 0) n = 0;
     if (n > p.cap) n = p.cap;
@@ -110,6 +110,12 @@ __global__ __launch_bounds__(256) void k_apply(ApplyArgs p) {
             id[r] = ok[r] ? p.ids[k[r]] : 0;
             if (ok[r] && (id[r] < 0 || id[r] >= p.vocab)) {
                 if (gl == 0) atomicOr(p.flags, (uint32_t) PXF_BAD_ID);
+                ok[r] = false;
+            }
+            // An id that repeats its neighbour's (any repeat, when the ids are sorted) would be updated by
+            // two lane groups at once: neither touches the row, and the flag is raised.
+            if (ok[r] && ((k[r] > 0 && p.ids[k[r] - 1] == id[r]) || (k[r] + 1 < n && p.ids[k[r] + 1] == id[r]))) {
+                if (gl == 0) atomicOr(p.flags, (uint32_t) PXF_NOT_UNIQUE);
                 ok[r] = false;
             }
         }

@@ -504,7 +504,7 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
            FB = FUSED ? B : 1, AB = MODE == MODE_ADAGRAD ? B : 1 };
     typedef typename std::conditional<VEC, float4, float>::type StateV;
     __shared__ double s_part[MERGE ? TPB * G * C * E : 1];
-    if (FUSED && (a.flags[0] & PXF_BAD_ID)) return;               // uniform: a bad id was seen, touch nothing
+    if (FUSED && a.flags[0]) return;                              // uniform: an error flag is up, touch nothing
 
     const int gl = threadIdx.x % G;
     const int gj = threadIdx.x / G;                               // tile inside the block
@@ -892,7 +892,7 @@ __device__ __forceinline__ void fixup_finish(const FixupArgs& a, uint32_t u, int
 
 __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
     __shared__ double s_red[FIX_SPLITS][64];
-    if (a.mode != MODE_ROWS && (a.flags[0] & PXF_BAD_ID)) return;   // uniform: a bad id was seen, touch nothing
+    if (a.mode != MODE_ROWS && a.flags[0]) return;                // uniform: an error flag is up, touch nothing
     const int lane = threadIdx.x & 63, split = threadIdx.x >> 6;
     const int64_t pe = (int64_t) blockIdx.y * 64 + lane;          // slot in the partial row
     // which column does slot pe hold?

@@ -117,5 +117,7 @@ extern "C" px_status px_device_status(px_ctx* ctx, void* hip_stream) {
     uint32_t f = ctx->h_flags[0];
     if (f & PXF_BAD_ID)
         return px_fail(ctx, PX_ERR_INDEX_OUT_OF_RANGE, "a row id outside [0, vocab) reached the device");
+    if (f & PXF_NOT_UNIQUE)
+        return px_fail(ctx, PX_ERR_NOT_UNIQUE, "an update was handed the same row id twice in a row");
     return PX_OK;
 }

@@ -55,6 +55,18 @@ double sampled(const double* p, const double* t, int n, double want) {
 
 extern "C" px_status px_partition_cost_fit(const double* p, const double* t, int n, double* theta) {
     if (!p || !t || !theta || n < 3) return PX_ERR_INVALID_ARG;
+    // Three parameters need three distinct partition counts: with fewer the normal equations are
+    // singular, which round-off can hide from a pivot test, so count them first.
+    double seen[3];
+    int n_seen = 0;
+    for (int i = 0; i < n && n_seen < 3; ++i) {
+        if (!(p[i] > 0)) return PX_ERR_INVALID_ARG;
+        bool is_new = true;
+        for (int j = 0; j < n_seen; ++j)
+            if (seen[j] == p[i]) is_new = false;
+        if (is_new) seen[n_seen++] = p[i];
+    }
+    if (n_seen < 3) return PX_ERR_INVALID_ARG;
     double a[3][3] = {{0, 0, 0}, {0, 0, 0}, {0, 0, 0}}, b[3] = {0, 0, 0};
     for (int i = 0; i < n; ++i) {
         if (!(p[i] > 0)) return PX_ERR_INVALID_ARG;

@@ -39,6 +39,8 @@ __device__ __forceinline__ uint4 load16(const uint4* p) {
 
 __device__ __forceinline__ uint16_t to_bf16(float f) {   // round to nearest, ties to even
     uint32_t u = __float_as_uint(f);
+    // a NaN stays a NaN (quiet bit set): the rounding bias would carry it into infinity or zero
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t) ((u >> 16) | 0x0040u);
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t) (u >> 16);
 }
@@ -199,9 +201,13 @@ void launch(px_ctx* ctx, const px_word_pack& pack, int n, int64_t count, bool ve
         }
         done = pieces * E;
     }
-    if (done < count)
-        k_dense_scalar<TIN, OUT_BF16, CARRIED><<<(unsigned) ((count - done + 255) / 256), 256, 0, stream>>>(
-            ctx->d_words, pack, n, done, count, out, scale);
+    // element-wise: unaligned buffers, or the tail behind the last full piece; at most 2^30 elements a launch
+    const int64_t scalar_chunk = (int64_t) 1 << 30;
+    for (; done < count; done += scalar_chunk) {
+        const int64_t last = done + scalar_chunk < count ? done + scalar_chunk : count;
+        k_dense_scalar<TIN, OUT_BF16, CARRIED><<<(unsigned) ((last - done + 255) / 256), 256, 0, stream>>>(
+            ctx->d_words, pack, n, done, last, out, scale);
+    }
 }
 
 template <bool CARRIED>

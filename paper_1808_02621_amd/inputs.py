@@ -110,10 +110,12 @@ def _worker_rngs(seed: int, n: int) -> List[np.random.Generator]:
 # ---------------------------------------------------------------- bf16 storage
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
-    """Round float32 to bfloat16 (nearest, ties to even); returns the uint16 patterns."""
+    """Round float32 to bfloat16 (nearest, ties to even; NaN stays NaN); returns the uint16 patterns."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
     bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
-    return ((u + bias) >> np.uint32(16)).astype(np.uint16)
+    rounded = ((u + bias) >> np.uint32(16)).astype(np.uint16)
+    nan = (u & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+    return np.where(nan, ((u >> np.uint32(16)) | np.uint32(0x0040)).astype(np.uint16), rounded)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:

@@ -156,7 +156,7 @@ class Context:
     # ------------------------------------------------------------------ calls
 
     def px_device_status(self, stream=None) -> int:
-        """Waits for the stream; returns PX_OK or PX_ERR_INDEX_OUT_OF_RANGE and clears the flag."""
+        """Waits for the stream; returns PX_OK, PX_ERR_INDEX_OUT_OF_RANGE or PX_ERR_NOT_UNIQUE and clears the flag."""
         return lib.px_device_status(self._h, _stream(stream))
 
     @staticmethod
@@ -171,19 +171,15 @@ class Context:
                            vocab: int, scale: float, out_ids: torch.Tensor, out_rows: torch.Tensor,
                            out_num_unique: torch.Tensor, out_run_len: Optional[torch.Tensor],
                            scratch: torch.Tensor, stream=None) -> None:
-        n = len(idx)
-        assert len(val) == n and n >= 1
-        code = _dtype_code(val[0])
-        counts = (ctypes.c_int64 * n)(*[int(i.numel()) for i in idx])
-        for i, v in zip(idx, val):
-            assert i.dtype == torch.int64 and i.is_contiguous() and v.is_contiguous()
-            assert _dtype_code(v) == code and v.numel() == i.numel() * dim
+        n, code, counts = self._coalesce_inputs(idx, val, dim)
         self._check(lib.px_sparse_coalesce(
             self._h, n, _ptr_array(idx), _ptr_array(val), counts, dim, code, vocab, scale,
             _ptr(out_ids), _ptr(out_rows), _ptr(out_num_unique), _ptr(out_run_len), _ptr(scratch),
             scratch.numel() * scratch.element_size(), _stream(stream)))
 
-    def _coalesce_inputs(self, idx, val, dim):
+    @staticmethod
+    def _coalesce_inputs(idx, val, dim):
+        """Worker count, value dtype code and the host array of per-worker row counts."""
         n = len(idx)
         assert len(val) == n and n >= 1
         code = _dtype_code(val[0])

@@ -107,6 +107,22 @@ def test_library_fit_and_argmin_match_the_oracle(px):
         px.px_partition_cost_fit([4, 4, 4], [1, 1, 1])           # one distinct P: singular
 
 
+@pytest.mark.parametrize("p", [[3, 7, 3, 7], [8, 16, 16, 8, 8], [4, 8, 4], [2, 64, 2], [5, 5, 9, 9, 9, 5]])
+def test_library_fit_rejects_two_distinct_partition_counts(px, p):
+    """Eq. 1 has three parameters: samples at two partition counts, however often each is repeated,
+    do not determine them (the oracle's design matrix has rank 2), and the library must say so
+    instead of returning whatever round-off leaves in a singular system."""
+    t = [1.0 + 0.37 * i for i in range(len(p))]
+    design = np.stack([np.ones(len(p)), 1.0 / np.array(p, dtype=np.float64), np.array(p, dtype=np.float64)], axis=1)
+    assert np.linalg.matrix_rank(design) == 2
+    with pytest.raises(px.PxError) as err:
+        px.px_partition_cost_fit(p, t)
+    assert err.value.status == px.PX_ERR_INVALID_ARG
+    # a third distinct count makes the same samples acceptable
+    got = px.px_partition_cost_fit(p + [11], t + [2.0])
+    assert np.allclose(got, cost_model.fit(p + [11], t + [2.0]), rtol=1e-7, atol=1e-9)
+
+
 def test_library_search_follows_the_same_samples(px):
     rng = np.random.default_rng(1)
     for trial in range(30):
@@ -123,3 +139,24 @@ def test_library_search_follows_the_same_samples(px):
             ts.append(float(cost_model.predict(theta, nxt)))
             assert len(ps) <= 64
         assert ps == [q for q, _ in ref]
+
+
+def test_recorded_search_check_on_flat_noisy_times(px):
+    """Times that hardly depend on P (what one GPU measures): the rule still visits the same counts
+    as the oracle and the two fits agree, whatever sign the fitted parameters take."""
+    import cost_model_checks
+    rng = np.random.default_rng(4)
+    for trial in range(20):
+        start = int(2 ** rng.integers(0, 5))
+        p_max = int(start * 2 ** rng.integers(1, 5))
+        noise = {}
+        ps, ts = [], []
+        while True:
+            nxt = px.px_partition_search_next(ps, ts, start, p_max)
+            if nxt == 0:
+                break
+            noise.setdefault(nxt, 200.0 + float(rng.normal(0, 1.0)))
+            ps.append(nxt)
+            ts.append(noise[nxt])
+            assert len(ps) <= 32
+        cost_model_checks.check_recorded_search(px, cost_model, ps, ts, start, p_max)

@@ -449,6 +449,54 @@ def test_out_of_range_id_raises_the_flag_and_protects_the_table(gpu):
     assert float(table[1, 0]) == -1.0 and float(table.abs().sum()) == dim
 
 
+def test_repeated_id_in_apply_is_reported_and_its_row_left_alone(gpu):
+    """Sec. 2.1: gradients are aggregated first, so that a row is updated once.  An id that repeats
+    (adjacent, as in any sorted list) is refused by the oracle; the library skips exactly those
+    positions, updates the others, and reports PX_ERR_NOT_UNIQUE once."""
+    ctx, px, runner = gpu
+    dim, vocab = 24, 50
+    rng = np.random.default_rng(17)
+    ids = np.array([2, 7, 7, 9, 20, 20, 20, 31], dtype=np.int64)
+    rows = rng.standard_normal((ids.size, dim)).astype(np.float32)
+    table = rng.standard_normal((vocab, dim)).astype(np.float32)
+    with pytest.raises(oracle.RepeatedId):
+        oracle.sparse_apply_sgd(table.copy(), ids, rows, 0.5)
+    keep = np.array([0, 3, 7])                                   # the positions whose id occurs once
+    for optimizer in ("sgd", "adagrad"):
+        ref_t, ref_a = table.copy(), np.full_like(table, 0.1)
+        d_t, d_a = torch.from_numpy(table).cuda(), torch.full((vocab, dim), 0.1, device="cuda")
+        num = torch.tensor([ids.size], dtype=torch.int64, device="cuda")
+        if optimizer == "sgd":
+            oracle.sparse_apply_sgd(ref_t, ids[keep], rows[keep], 0.5)
+            ctx.px_sparse_apply_sgd(d_t, runner.to_device(ids), runner.to_device(rows), num, ids.size, None, None, 0.5)
+        else:
+            oracle.sparse_apply_adagrad(ref_t, ref_a, ids[keep], rows[keep], 0.5)
+            ctx.px_sparse_apply_adagrad(d_t, d_a, runner.to_device(ids), runner.to_device(rows), num, ids.size,
+                                        None, None, 0.5)
+        assert ctx.px_device_status() == px.PX_ERR_NOT_UNIQUE
+        assert ctx.px_device_status() == px.PX_OK                # reported once, then cleared
+        close(d_t.cpu().numpy(), ref_t)
+        close(d_a.cpu().numpy(), ref_a)
+        for r in (7, 20):                                        # the repeated ids' rows: bit-identical
+            assert np.array_equal(d_t[r].cpu().numpy(), table[r])
+    # while the flag is up, later updates on the context leave their table alone
+    ids2 = torch.tensor([1, 1, 4], dtype=torch.int64, device="cuda")
+    rows2 = torch.ones((3, dim), device="cuda")
+    num2 = torch.tensor([3], dtype=torch.int64, device="cuda")
+    t2 = torch.zeros((vocab, dim), device="cuda")
+    ctx.px_sparse_apply_sgd(t2, ids2, rows2, num2, 3, None, None, 1.0)
+    ids3 = torch.tensor([5, 6], dtype=torch.int64, device="cuda")
+    ctx.px_sparse_apply_sgd(t2, ids3, rows2, torch.tensor([2], dtype=torch.int64, device="cuda"), 2, None, None, 1.0)
+    assert float(t2[4, 0]) == -1.0 and float(t2.abs().sum()) == dim        # only id 4 of the first call
+    assert ctx.px_device_status() == px.PX_ERR_NOT_UNIQUE
+    # distinct ids in any order are fine, and so is the last position equalling nothing
+    ids4 = np.array([40, 3, 12, 11], dtype=np.int64)
+    t4 = torch.zeros((vocab, dim), device="cuda")
+    ctx.px_sparse_apply_sgd(t4, runner.to_device(ids4), torch.ones((4, dim), device="cuda"),
+                            torch.tensor([4], dtype=torch.int64, device="cuda"), 4, None, None, 1.0)
+    assert ctx.px_device_status() == px.PX_OK and float(t4.sum()) == -4.0 * dim
+
+
 def test_host_side_argument_errors(gpu):
     ctx, px, runner = gpu
     dim, vocab = 16, 100
@@ -495,6 +543,55 @@ def test_two_level_aggregation(gpu):
     t_ids, t_rows, _ = oracle.sparse_coalesce(gi, gv, w.dim, w.vocab)
     x, ref = second.out_rows[:u].cpu().numpy(), t_rows
     assert np.all(np.abs(x - ref) <= 2 * np.spacing(np.abs(ref)))
+
+
+def test_partition_search_on_measured_chain_times(gpu):
+    """Sec. 3.2, Eq. 1 on this machine: the library's sampling rule is driven by times of the sparse
+    chain measured on the device; the recorded (P, time) list is then handed to the oracle, which
+    must visit the same partition counts in the same order, fit the same theta and pick the same P."""
+    import cost_model_checks
+    ctx, px, runner = gpu
+    from oracle import cost_model
+    w = inputs.shrink(inputs.LARGE_LM, vocab=200_000, n_per_worker=1_000)
+    d_idx = [runner.to_device(i) for i in inputs.sparse_ids(w)]
+    d_val = [runner.to_device(v) for v in inputs.sparse_values(w)]
+    table = torch.zeros((w.vocab, w.dim), device="cuda")
+    accum = torch.full((w.vocab, w.dim), w.accum_init, device="cuda")
+
+    def measure(n_shards):
+        b = runner.sparse_buffers(d_idx, d_val, w.dim, w.vocab, n_shards, px.PX_HASH_MUL)
+        times = []
+        for it in range(8):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            runner.sparse_step(ctx, b, table, accum, w.optimizer, w.lr)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e3)
+        return float(np.median(times[2:]))
+
+    for start, p_max in ((8, 256), (2, 16)):
+        ps, ts = [], []
+        while True:
+            nxt = px.px_partition_search_next(ps, ts, start, p_max)
+            if nxt == 0:
+                break
+            assert nxt not in ps and 1 <= nxt <= p_max and len(ps) < 16
+            ps.append(nxt)
+            ts.append(measure(nxt))
+        cost_model_checks.check_recorded_search(px, cost_model, ps, ts, start, p_max)
+    assert ctx.px_device_status() == px.PX_OK
+
+
+def test_cost_model_library_against_the_oracle_on_this_box():
+    """The host-only comparisons of the cost model, collected by the GPU run as well (they need no
+    device, but the library they load is the one the GPU tests use)."""
+    import test_cost_model
+    from paper_1808_02621_amd import px
+    test_cost_model.test_library_fit_and_argmin_match_the_oracle(px)
+    test_cost_model.test_library_search_follows_the_same_samples(px)
+    for p in ([3, 7, 3, 7], [8, 16, 16, 8, 8]):
+        test_cost_model.test_library_fit_rejects_two_distinct_partition_counts(px, p)
 
 
 def test_whole_path_replays_from_a_hip_graph(gpu):
@@ -760,25 +857,68 @@ def test_dense_average_integers_are_exact(gpu):
 
 
 def test_dense_average_full_size_sampled(gpu):
-    """48 x 64M bf16 (the NMT-like dense part) in the benchmark's launch shape; the oracle
-    recomputes three windows and a scattered sample of the outputs."""
+    """48 x 64M bf16 (the NMT-like dense part) in the benchmark's launch shape (16 launches of 2^22
+    output elements, each die working on a contiguous 2^19 of them).  Every worker's buffer is a
+    seeded block whose length is odd, rolled by its own shift and repeated, so neither the inputs nor
+    the expected output repeat with the launch length or any part of it: a launch, or a die's
+    eighth of one, that read or wrote a whole number of its lengths away would be seen.  The oracle
+    recomputes windows at both ends, across the borders of launches and of the dies' eighths, and
+    a scattered sample."""
     ctx, px, runner = gpu
     w = inputs.NMT
     count = w.dense_count
-    block = inputs.dense_buffer(w, inputs.dense_rngs(w)[0], 1 << 22)       # 4M-element seeded block
+    launch = 1 << 22
+    assert px.px_dense_average_launches(w.n_workers, count, True) == count // launch
+    period = launch - 37                                                   # odd: coprime to every power of two
+    block = inputs.dense_buffer(w, inputs.dense_rngs(w)[0], period)
     base = runner.to_device(block)
     g = torch.Generator(device="cuda").manual_seed(1808)
     d = []
-    for k in range(w.n_workers):                                           # each worker: its own shuffle
-        shift = int(torch.randint(0, 1 << 22, (1,), generator=g, device="cuda").item())
-        d.append(torch.roll(base, shift).repeat(count >> 22))
+    for k in range(w.n_workers):                                           # each worker: its own shift
+        shift = int(torch.randint(0, period, (1,), generator=g, device="cuda").item())
+        d.append(torch.roll(base, shift).repeat(count // period + 1)[:count].contiguous())
+    # the expected output at j and at j + launch differ (spot check of the construction itself)
+    assert not torch.equal(d[0][:4096], d[0][launch:launch + 4096])
     out = torch.empty(count, dtype=torch.float32, device="cuda")
     ctx.px_dense_average(d, count, out, 1.0 / w.n_workers)
     rng = np.random.default_rng(5)
-    picks = [np.arange(0, 4096), np.arange(count // 2 - 777, count // 2 + 777),
-             np.arange(count - 4096, count), np.sort(rng.integers(0, count, size=20_000))]
+    picks = [np.arange(0, 4096), np.arange(count // 2 - 777, count // 2 + 777), np.arange(count - 4096, count)]
+    for k in (1, 2, 5, 8, 11, 15):                                          # borders between launches
+        picks.append(np.arange(k * launch - 1024, k * launch + 1024))
+    for k in (1, 3, 9, 20, 63, 127):                                        # borders between the dies' eighths
+        picks.append(np.arange(k * (launch >> 3) - 512, k * (launch >> 3) + 512))
+    picks.append(np.sort(rng.integers(0, count, size=40_000)))
     for sel in picks:
         t = torch.from_numpy(sel).cuda()
         host = [x[t].view(torch.int16).cpu().numpy().view(np.uint16) for x in d]
-        close(out[t].cpu().numpy(), oracle.dense_average(host, average=True), rel=1e-2)
         close(out[t].cpu().numpy(), oracle.dense_average(host, average=True))
+
+
+def test_dense_average_nan_and_inf_with_bf16_output(gpu):
+    """A NaN or an infinity in a gradient stays one in the reduced buffer, also when the output is
+    rounded to bfloat16 (the rounding bias must not carry a NaN pattern into infinity or zero)."""
+    ctx, px, runner = gpu
+    count = 4096 + 3
+    a = np.zeros(count, dtype=np.float32)
+    b = np.ones(count, dtype=np.float32)
+    a[5], a[77], a[4097] = np.inf, -np.inf, np.inf
+    nan_bits = np.array([0x7F800001, 0xFFFFFFFF, 0x7FC00000, 0xFF80FFFF], dtype=np.uint32).view(np.float32)
+    a[100:104] = nan_bits
+    a[4098] = nan_bits[0]
+    for out_dtype in (torch.bfloat16, torch.float32):
+        out = torch.empty(count, dtype=out_dtype, device="cuda")
+        ctx.px_dense_average([runner.to_device(a), runner.to_device(b)], count, out, 1.0)
+        got = out.float().cpu().numpy()
+        ref = oracle.dense_average([a, b], average=False)
+        assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.isnan(got).sum() == 5
+        assert np.array_equal(np.isinf(got), np.isinf(ref)) and np.array_equal(got[np.isinf(got)], ref[np.isinf(ref)])
+        fin = np.isfinite(ref)
+        close(got[fin], ref[fin], 1e-2 if out_dtype == torch.bfloat16 else REL_TOL)
+    # one buffer, scale 1, bfloat16 output: the library's rounding is the host recipe's, bit for bit
+    out = torch.empty(count, dtype=torch.bfloat16, device="cuda")
+    ctx.px_dense_average([runner.to_device(a)], count, out, 1.0)
+    got_bits = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    want = torch.from_numpy(a).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    ok = ~np.isnan(a)
+    assert np.array_equal(got_bits[ok], want[ok])
+    assert np.isnan(inputs.bf16_bits_to_f32(got_bits[~ok])).all()

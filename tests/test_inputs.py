@@ -49,3 +49,19 @@ def test_bf16_round_trip():
     back = inputs.bf16_bits_to_f32(bits)
     # 1 + 2^-8 is a tie -> even (1.0); 1 + 3*2^-8 is a tie -> even (1 + 2^-6)
     assert back.tolist() == [1.0, 1.0, 1.015625, -2.5, 0.0, 3.140625]
+
+
+def test_bf16_rounding_agrees_with_pytorch_including_nan_and_inf():
+    import torch
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(100_000).astype(np.float32) * np.float32(10.0) ** rng.integers(-20, 20, 100_000).astype(np.float32)
+    special = np.array([np.inf, -np.inf, 0.0, -0.0, 3.3895314e38, -3.3895314e38], dtype=np.float32)
+    nans = np.array([0x7F800001, 0xFFFFFFFF, 0x7FC00000, 0x7F80FFFF, 0xFF800001, 0x7FFFFFFF], dtype=np.uint32).view(np.float32)
+    x = np.concatenate([x, special, nans])
+    bits = inputs.f32_to_bf16_bits(x)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    finite = ~np.isnan(x)
+    assert np.array_equal(bits[finite], ref[finite])              # round to nearest even, overflow to infinity
+    back = inputs.bf16_bits_to_f32(bits)
+    assert np.isnan(back[~finite]).all() and not np.isnan(back[finite]).any()
+    assert np.array_equal(np.signbit(back[~finite]), np.signbit(x[~finite]))
