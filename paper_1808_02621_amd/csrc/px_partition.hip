@@ -48,29 +48,19 @@ struct ShardPass {
 
 }  // namespace
 
-extern "C" size_t px_partition_scratch_bytes(int64_t cap) {
-    if (cap < 0) return 0;
-    return px_align_up((size_t) PX_SORT_MAX_BLOCKS * 256 * 4, 256) + px_align_up(256 * 4, 256);
-}
+// Scratch of a partition call: the per-block histogram matrix, then the per-bin totals.
+enum : size_t {
+    PART_HIST_BYTES = (size_t) PX_SORT_MAX_BLOCKS * 256 * 4,          // a multiple of 256
+    PART_TOTALS_BYTES = 256 * 4,
+    PART_SCRATCH_BYTES = PART_HIST_BYTES + PART_TOTALS_BYTES
+};
+static_assert(PART_HIST_BYTES % 256 == 0, "the totals start 256-byte aligned");
 
-extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids,
-                                       int64_t cap, int num_shards, px_hash hash, int32_t* out_shard,
-                                       int32_t* out_perm, int64_t* out_offsets, void* scratch,
-                                       size_t scratch_bytes, void* hip_stream) {
-    if (!ctx) return PX_ERR_INVALID_ARG;
-    hipStream_t stream = (hipStream_t) hip_stream;
-    if (num_shards < 1 || num_shards > PX_MAX_SHARDS)
-        return px_fail(ctx, PX_ERR_INVALID_ARG, "num_shards %d outside [1, %d]", num_shards, (int) PX_MAX_SHARDS);
-    if (hash != PX_HASH_MOD && hash != PX_HASH_MUL) return px_fail(ctx, PX_ERR_INVALID_ARG, "unknown hash %d", (int) hash);
-    if (cap < 0 || cap >= (1ll << 31)) return px_fail(ctx, PX_ERR_INVALID_ARG, "cap %lld outside [0, 2^31)", (long long) cap);
-    if (!num_ids || !out_offsets || !scratch || (cap > 0 && (!ids || !out_perm)))
-        return px_fail(ctx, PX_ERR_INVALID_ARG, "null argument");
-    if (((uintptr_t) scratch) % 256) return px_fail(ctx, PX_ERR_INVALID_ARG, "scratch needs 256-byte alignment");
-    const size_t need = px_partition_scratch_bytes(cap);
-    if (scratch_bytes < need) return px_fail(ctx, PX_ERR_SCRATCH_TOO_SMALL, "scratch %zu < %zu bytes", scratch_bytes, need);
-
+static px_status partition_common(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids, int64_t cap,
+                                  int num_shards, px_hash hash, int32_t* out_shard, int32_t* out_perm,
+                                  int64_t* out_offsets, void* scratch, hipStream_t stream) {
     uint32_t* hist = (uint32_t*) scratch;
-    uint32_t* totals = (uint32_t*) ((char*) scratch + px_align_up((size_t) PX_SORT_MAX_BLOCKS * 256 * 4, 256));
+    uint32_t* totals = (uint32_t*) ((char*) scratch + PART_HIST_BYTES);
     const px_sort_geom g = px_sort_geometry(cap);
     ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard, out_offsets};
     pxr::k_radix_hist<ShardPass, 8><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.chunk);
@@ -78,4 +68,37 @@ extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const in
     if (!own) pxr::k_radix_prefix<<<256 / 4, 256, 0, stream>>>(hist, g.n_blocks, 256, totals);
     pxr::k_radix_scatter<ShardPass, 8><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, totals, g.chunk, own);
     return px_check_hip(ctx, hipGetLastError(), "partition launch");
+}
+
+// Host-side argument checks shared by the two entry points.
+static px_status partition_check(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids, int64_t cap,
+                                 int num_shards, px_hash hash, const int32_t* out_perm,
+                                 const int64_t* out_offsets) {
+    if (num_shards < 1 || num_shards > PX_MAX_SHARDS)
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "num_shards %d outside [1, %d]", num_shards, (int) PX_MAX_SHARDS);
+    if (hash != PX_HASH_MOD && hash != PX_HASH_MUL) return px_fail(ctx, PX_ERR_INVALID_ARG, "unknown hash %d", (int) hash);
+    if (cap < 0 || cap >= (1ll << 31)) return px_fail(ctx, PX_ERR_INVALID_ARG, "cap %lld outside [0, 2^31)", (long long) cap);
+    if (!num_ids || !out_offsets || (cap > 0 && (!ids || !out_perm)))
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "null argument");
+    return PX_OK;
+}
+
+extern "C" size_t px_partition_scratch_bytes(int64_t cap) {
+    if (cap < 0) return 0;
+    return PART_SCRATCH_BYTES;
+}
+
+extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids,
+                                       int64_t cap, int num_shards, px_hash hash, int32_t* out_shard,
+                                       int32_t* out_perm, int64_t* out_offsets, void* scratch,
+                                       size_t scratch_bytes, void* hip_stream) {
+    if (!ctx) return PX_ERR_INVALID_ARG;
+    px_status st = partition_check(ctx, ids, num_ids, cap, num_shards, hash, out_perm, out_offsets);
+    if (st != PX_OK) return st;
+    if (!scratch) return px_fail(ctx, PX_ERR_INVALID_ARG, "null argument");
+    if (((uintptr_t) scratch) % 256) return px_fail(ctx, PX_ERR_INVALID_ARG, "scratch needs 256-byte alignment");
+    const size_t need = px_partition_scratch_bytes(cap);
+    if (scratch_bytes < need) return px_fail(ctx, PX_ERR_SCRATCH_TOO_SMALL, "scratch %zu < %zu bytes", scratch_bytes, need);
+    return partition_common(ctx, ids, num_ids, cap, num_shards, hash, out_shard, out_perm, out_offsets, scratch,
+                            (hipStream_t) hip_stream);
 }
