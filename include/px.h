@@ -69,7 +69,8 @@ typedef enum { PX_HASH_MOD = 0, PX_HASH_MUL = 1 } px_hash;
 
 enum {
     PX_MAX_SOURCES = 1024, /* most workers / dense buffers in one call */
-    PX_MAX_SHARDS = 256    /* most shards in one px_partition_rows call (Table 2 sweeps 8..256) */
+    PX_MAX_SHARDS = 256,   /* most shards in one px_partition_rows call (Table 2 sweeps 8..256) */
+    PX_PARTITION_NOALLOC_MAX_IDS = 1 << 22 /* largest cap px_partition_rows_noalloc accepts */
 };
 
 /* Create a context on GPU `device`.  Allocates a few hundred KB of device and
@@ -144,6 +145,21 @@ px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const int64_t* num_
                             int num_shards, px_hash hash, int32_t* out_shard, int32_t* out_perm,
                             int64_t* out_offsets, void* scratch, size_t scratch_bytes,
                             void* hip_stream);
+
+/*
+ * px_partition_rows for callers that can neither allocate device memory nor hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments (without scratch), same kernels, same results bit for bit.  The workspace is
+ * an array built into the library, 513 KiB on every GPU it runs on, held until the process
+ * ends; its device address is looked up once per GPU, when px_create runs there.  The call
+ * allocates and frees nothing.  Limits: cap <= PX_PARTITION_NOALLOC_MAX_IDS (4,194,304 ids; a
+ * larger cap is refused with PX_ERR_INVALID_ARG before anything is enqueued: use
+ * px_partition_rows).  All contexts on a GPU share that GPU's array: calls of this entry point
+ * that overlap on one GPU (two streams, two contexts) race and must be ordered by the caller.
+ */
+px_status px_partition_rows_noalloc(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids,
+                                    int64_t cap, int num_shards, px_hash hash, int32_t* out_shard,
+                                    int32_t* out_perm, int64_t* out_offsets, void* hip_stream);
 
 /*
  * Sparse variable update by gradient descent (Fig. 4; Sec. 2.1: gradients are

@@ -66,6 +66,7 @@ extern "C" px_status px_create(px_ctx** out, int device) {
     if (e == hipSuccess) e = hipHostMalloc((void**) &ctx->h_flags, 64 * sizeof(uint32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMemset(ctx->d_flags, 0, 64 * sizeof(uint32_t));
     if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess && px_partition_noalloc_setup(ctx) != PX_OK) e = hipErrorInvalidSymbol;
     (void) hipSetDevice(prev);
     if (e != hipSuccess) {
         px_destroy(ctx);

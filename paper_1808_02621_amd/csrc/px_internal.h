@@ -13,6 +13,7 @@ struct px_ctx {
     uint64_t* d_words;   // device: pointer / offset tables uploaded per call
     uint32_t* d_flags;   // device: [0] sticky error flag
     uint32_t* h_flags;   // pinned host mirror for px_device_status
+    void* part_scratch;  // device address of the partition's built-in scratch on this GPU (not owned)
     char err[512];
 };
 
@@ -24,6 +25,8 @@ enum { PXF_BAD_ID = 1u, PXF_NOT_UNIQUE = 2u };   // bits of d_flags[0]; any set 
 
 px_status px_fail(px_ctx* ctx, px_status s, const char* fmt, ...);
 px_status px_check_hip(px_ctx* ctx, hipError_t e, const char* what);
+// Looks up the device address of the partition's built-in scratch; ctx->device must be current.
+px_status px_partition_noalloc_setup(px_ctx* ctx);
 
 // Up to PX_UPLOAD_WORDS 64-bit words can ride inside the arguments of a kernel launch.
 enum { PX_UPLOAD_WORDS = 256 };

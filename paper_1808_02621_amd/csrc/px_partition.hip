@@ -7,6 +7,8 @@
 // shard; the scan of the per-shard totals is the offsets array.  The number of
 // ids is a device scalar: the grid is sized for the capacity and every block
 // clamps to the real count.
+#include <mutex>
+
 #include "px_radix.h"
 
 namespace {
@@ -58,9 +60,9 @@ static_assert(PART_HIST_BYTES % 256 == 0, "the totals start 256-byte aligned");
 
 static px_status partition_common(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids, int64_t cap,
                                   int num_shards, px_hash hash, int32_t* out_shard, int32_t* out_perm,
-                                  int64_t* out_offsets, void* scratch, hipStream_t stream) {
-    uint32_t* hist = (uint32_t*) scratch;
-    uint32_t* totals = (uint32_t*) ((char*) scratch + PART_HIST_BYTES);
+                                  int64_t* out_offsets, void* work, hipStream_t stream) {
+    uint32_t* hist = (uint32_t*) work;
+    uint32_t* totals = (uint32_t*) ((char*) work + PART_HIST_BYTES);
     const px_sort_geom g = px_sort_geometry(cap);
     ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard, out_offsets};
     pxr::k_radix_hist<ShardPass, 8><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.chunk);
@@ -90,15 +92,62 @@ extern "C" size_t px_partition_scratch_bytes(int64_t cap) {
 
 extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids,
                                        int64_t cap, int num_shards, px_hash hash, int32_t* out_shard,
-                                       int32_t* out_perm, int64_t* out_offsets, void* scratch,
-                                       size_t scratch_bytes, void* hip_stream) {
+                                       int32_t* out_perm, int64_t* out_offsets, void* work,
+                                       size_t work_bytes, void* hip_stream) {
     if (!ctx) return PX_ERR_INVALID_ARG;
     px_status st = partition_check(ctx, ids, num_ids, cap, num_shards, hash, out_perm, out_offsets);
     if (st != PX_OK) return st;
-    if (!scratch) return px_fail(ctx, PX_ERR_INVALID_ARG, "null argument");
-    if (((uintptr_t) scratch) % 256) return px_fail(ctx, PX_ERR_INVALID_ARG, "scratch needs 256-byte alignment");
+    if (!work) return px_fail(ctx, PX_ERR_INVALID_ARG, "null argument");
+    if (((uintptr_t) work) % 256) return px_fail(ctx, PX_ERR_INVALID_ARG, "scratch needs 256-byte alignment");
     const size_t need = px_partition_scratch_bytes(cap);
-    if (scratch_bytes < need) return px_fail(ctx, PX_ERR_SCRATCH_TOO_SMALL, "scratch %zu < %zu bytes", scratch_bytes, need);
-    return partition_common(ctx, ids, num_ids, cap, num_shards, hash, out_shard, out_perm, out_offsets, scratch,
+    if (work_bytes < need) return px_fail(ctx, PX_ERR_SCRATCH_TOO_SMALL, "scratch %zu < %zu bytes", work_bytes, need);
+    return partition_common(ctx, ids, num_ids, cap, num_shards, hash, out_shard, out_perm, out_offsets, work,
                             (hipStream_t) hip_stream);
+}
+
+// ------------------------------------------------------- the variant that allocates nothing
+// For callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+// capture, tight serving loops, harnesses that forbid hipMalloc): the histogram matrix and the
+// totals live in this array, PART_SCRATCH_BYTES (513 KiB) on every GPU the library runs on, until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// kernels get the device address that call returned, looked up once per GPU when a context is
+// created there.  Every context on a GPU shares that GPU's copy, so calls of this entry point
+// that overlap on one GPU race.  Nothing in it has to start at zero: every launch writes the
+// histogram rows and totals it later reads.
+static __device__ __align__(256) unsigned char scratch[PART_SCRATCH_BYTES];
+
+enum { PART_MAX_DEVICES = 64 };
+static void* g_scratch_address[PART_MAX_DEVICES];     // device address of `scratch` on GPU d, null until looked up
+static std::mutex g_scratch_mutex;
+
+// Called by px_create with ctx->device current.
+px_status px_partition_noalloc_setup(px_ctx* ctx) {
+    if (ctx->device < 0 || ctx->device >= PART_MAX_DEVICES) {
+        ctx->part_scratch = nullptr;                    // the entry point will refuse
+        return PX_OK;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_address[ctx->device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress((void**) &ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return px_check_hip(ctx, e != hipSuccess ? e : hipErrorInvalidSymbol, "built-in scratch lookup");
+        g_scratch_address[ctx->device] = ptr;
+    }
+    ctx->part_scratch = g_scratch_address[ctx->device];
+    return PX_OK;
+}
+
+extern "C" px_status px_partition_rows_noalloc(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids,
+                                               int64_t cap, int num_shards, px_hash hash, int32_t* out_shard,
+                                               int32_t* out_perm, int64_t* out_offsets, void* hip_stream) {
+    if (!ctx) return PX_ERR_INVALID_ARG;
+    px_status st = partition_check(ctx, ids, num_ids, cap, num_shards, hash, out_perm, out_offsets);
+    if (st != PX_OK) return st;
+    if (cap > (int64_t) PX_PARTITION_NOALLOC_MAX_IDS)
+        return px_fail(ctx, PX_ERR_INVALID_ARG, "cap %lld is more than the %lld ids the built-in scratch serves; "
+                       "use px_partition_rows with a workspace", (long long) cap, (long long) PX_PARTITION_NOALLOC_MAX_IDS);
+    if (!ctx->part_scratch)
+        return px_fail(ctx, PX_ERR_DEVICE, "the built-in scratch was not found on GPU %d when the context was created", ctx->device);
+    return partition_common(ctx, ids, num_ids, cap, num_shards, hash, out_shard, out_perm, out_offsets,
+                            ctx->part_scratch, (hipStream_t) hip_stream);
 }

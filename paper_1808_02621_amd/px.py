@@ -29,6 +29,7 @@ PX_F32, PX_BF16 = 0, 1
 PX_HASH_MOD, PX_HASH_MUL = 0, 1
 PX_MAX_SOURCES = 1024
 PX_MAX_SHARDS = 256
+PX_PARTITION_NOALLOC_MAX_IDS = 1 << 22
 
 EXPORTS = [
     "px_create", "px_destroy", "px_status_string", "px_last_error", "px_device_status",
@@ -36,7 +37,7 @@ EXPORTS = [
     "px_partition_rows", "px_sparse_apply_sgd", "px_sparse_apply_adagrad", "px_dense_average",
     "px_sparse_coalesce_apply_sgd", "px_sparse_coalesce_apply_adagrad", "px_sparse_lookup",
     "px_partition_cost_fit", "px_partition_cost_argmin", "px_partition_search_next",
-    "px_dense_average_launches",
+    "px_dense_average_launches", "px_partition_rows_noalloc",
 ]
 
 if not os.path.exists(LIBRARY):
@@ -78,6 +79,8 @@ lib.px_sparse_lookup.restype = _int
 lib.px_sparse_lookup.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp]
 lib.px_partition_rows.restype = _int
 lib.px_partition_rows.argtypes = [_vp, _vp, _vp, _i64, _int, _int, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.px_partition_rows_noalloc.restype = _int
+lib.px_partition_rows_noalloc.argtypes = [_vp, _vp, _vp, _i64, _int, _int, _vp, _vp, _vp, _vp]
 lib.px_sparse_apply_sgd.restype = _int
 lib.px_sparse_apply_sgd.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _f32, _vp]
 lib.px_sparse_apply_adagrad.restype = _int
@@ -223,6 +226,14 @@ class Context:
         self._check(lib.px_partition_rows(
             self._h, _ptr(ids), _ptr(num_ids), cap, num_shards, hash, _ptr(out_shard), _ptr(out_perm),
             _ptr(out_offsets), _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+    def px_partition_rows_noalloc(self, ids: torch.Tensor, num_ids: torch.Tensor, cap: int, num_shards: int,
+                                  hash: int, out_shard: Optional[torch.Tensor], out_perm: torch.Tensor,
+                                  out_offsets: torch.Tensor, stream=None) -> None:
+        """px_partition_rows on the library's built-in scratch: allocates nothing, cap limited."""
+        self._check(lib.px_partition_rows_noalloc(
+            self._h, _ptr(ids), _ptr(num_ids), cap, num_shards, hash, _ptr(out_shard), _ptr(out_perm),
+            _ptr(out_offsets), _stream(stream)))
 
     def px_sparse_apply_sgd(self, table: torch.Tensor, ids: torch.Tensor, rows: torch.Tensor,
                             num_ids: torch.Tensor, cap: int, perm: Optional[torch.Tensor],
