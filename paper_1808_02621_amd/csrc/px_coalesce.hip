@@ -104,7 +104,7 @@ struct Scratch {
     uint64_t* keys_b;
     uint32_t* hist;        // [PX_SORT_MAX_BLOCKS][bins], bins <= PX_RADIX_MAX
     uint32_t* totals;      // [bins] items per digit
-    uint32_t* hcount;      // heads per 2048-row block
+    uint32_t* hcount;      // heads per 2048-row block, top bit: published (written by the head-ranking kernel)
     uint32_t* run_start;   // [M + 1]
     uint4* tile_info;      // [n_tiles] first row, flags, run index of the first row
     uint4* span_long;      // [n_tiles] split runs over more than SPAN_LONG_TILES tiles
@@ -162,7 +162,8 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__
                                                           int n_workers, int64_t m, int64_t vocab,
                                                           int local_bits, uint64_t* __restrict__ keys,
                                                           uint32_t* __restrict__ hist, int64_t chunk,
-                                                          uint32_t* __restrict__ flags) {
+                                                          uint32_t* __restrict__ flags,
+                                                          uint32_t* __restrict__ hpub) {
     __shared__ uint32_t s_prefix[PX_MAX_SOURCES + 1];
     __shared__ uint64_t s_idx[CARRIED ? PX_UPLOAD_WORDS / 3 + 1 : 1];
     enum { BINS = 1 << BITS };
@@ -183,6 +184,8 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__
     const int64_t begin = (int64_t) blockIdx.x * chunk;
     int64_t end = begin + chunk;
     if (end > m) end = m;
+    // the head-ranking kernel publishes one word per PX_SORT_TILE rows: clear those of this chunk
+    for (int64_t h = begin / PX_SORT_TILE + tid; h * PX_SORT_TILE < end; h += PX_SORT_THREADS) hpub[h] = 0u;
     // PX_SORT_ITEMS rows per thread at a time: their ids are requested together
     for (int64_t p0 = begin + tid; p0 < end; p0 += (int64_t) PX_SORT_THREADS * PX_SORT_ITEMS) {
         uint32_t local[PX_SORT_ITEMS];
@@ -241,32 +244,25 @@ struct SortWords {
 
 // --------------------------------------------------------------------- heads
 
-__global__ __launch_bounds__(256) void k_heads_count(const uint64_t* __restrict__ sorted, int64_t m,
-                                                     uint32_t* __restrict__ hcount) {
-    __shared__ uint32_t s_cnt;
-    if (threadIdx.x == 0) s_cnt = 0u;
-    __syncthreads();
-    const int64_t base = (int64_t) blockIdx.x * PX_SORT_TILE;
-    uint32_t c = 0;
-#pragma unroll
-    for (int j = 0; j < PX_SORT_ITEMS; ++j) {
-        const int64_t i = base + j * 256 + threadIdx.x;
-        if (i < m) c += (i == 0 || key_of(sorted[i]) != key_of(sorted[i - 1])) ? 1u : 0u;
-    }
-    for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o);
-    if (pxr::lane_id() == 0) atomicAdd(&s_cnt, c);
-    __syncthreads();
-    if (threadIdx.x == 0) hcount[blockIdx.x] = s_cnt;
-}
-
 // Ranks the heads: distinct ids, run starts, U; and for every window of tile_rows rows the tile
 // that starts there: its first row (the first head in the leading part of the window, else the
 // window's own first row), the run that row belongs to, and the first head at or after that row
 // inside the window.  It also writes every row's reference for the segmented sum: the address of
 // its value row, with bit 0 set when the row is the last of its run (value rows are at least
 // 2-byte aligned, so the bit is free).
+//
+// The rank of a head needs the number of heads in all blocks before this one.  Every block
+// publishes its own count in hpub (cleared by the pack kernel) with the top bit as the "valid"
+// mark, then reads the words of all blocks before it, waiting for those not yet valid.  A block
+// only ever waits for blocks with smaller numbers, which the hardware starts no later than it, and
+// those never wait for it; the wait is bounded all the same, and a block that gives up raises
+// PXF_INTERNAL.  The words are written and read with device-scope atomic accesses, which the
+// dies' separate L2 caches do not hold back.
+#ifndef PX_HEADS_SPIN_LIMIT
+#define PX_HEADS_SPIN_LIMIT (1 << 18)
+#endif
 __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__ sorted, int64_t m,
-                                                    const uint32_t* __restrict__ hcount, int tile_rows,
+                                                    uint32_t* __restrict__ hpub, int tile_rows,
                                                     const uint64_t* __restrict__ words, int n_workers,
                                                     int local_bits, int64_t row_bytes,
                                                     uint64_t* __restrict__ rowref,
@@ -274,7 +270,7 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
                                                     uint32_t* __restrict__ run_start,
                                                     uint4* __restrict__ tile_info,
                                                     int64_t* __restrict__ out_num_unique,
-                                                    const uint32_t* __restrict__ flags) {
+                                                    uint32_t* __restrict__ flags) {
     __shared__ uint32_t s_wave[4];
     __shared__ uint32_t s_first[PX_SORT_TILE / 32];        // first aligning head of each window of this block
     __shared__ uint32_t s_head[PX_SORT_TILE / 32];         // first head of the window, 0xffffffff if it has none
@@ -285,11 +281,7 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
         s_head[tid] = 0xffffffffu;
     }
     for (int i = tid; i < n_workers; i += 256) s_vbase[i] = words[n_workers + i];
-    // heads in all blocks before this one
-    uint32_t part = 0;
-    for (int b = tid; b < (int) blockIdx.x; b += 256) part += hcount[b];
-    uint32_t before;
-    pxr::block_exclusive_scan_256(part, s_wave, &before);
+    __syncthreads();
 
     const uint32_t block_base = blockIdx.x * (uint32_t) PX_SORT_TILE;
     const int64_t base = (int64_t) block_base + (int64_t) tid * PX_SORT_ITEMS;
@@ -318,7 +310,26 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
         cnt += flag[j];
     }
     uint32_t block_total;
-    uint32_t rank = before + pxr::block_exclusive_scan_256(cnt, s_wave, &block_total);   // syncs
+    uint32_t rank = pxr::block_exclusive_scan_256(cnt, s_wave, &block_total);   // syncs
+    if (tid == 0)
+        __hip_atomic_store(&hpub[blockIdx.x], 0x80000000u | block_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // heads in all blocks before this one
+    uint32_t part = 0;
+    for (int b = tid; b < (int) blockIdx.x; b += 256) {
+        uint32_t v = __hip_atomic_load(&hpub[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int spin = 0; !(v & 0x80000000u) && spin < PX_HEADS_SPIN_LIMIT; ++spin) {
+            __builtin_amdgcn_s_sleep(2);
+            v = __hip_atomic_load(&hpub[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (!(v & 0x80000000u)) {
+            atomicOr(flags, (uint32_t) PXF_INTERNAL);      // never seen: the ranks of this call are wrong, and say so
+            v = 0u;
+        }
+        part += v & 0x7fffffffu;
+    }
+    uint32_t before;
+    pxr::block_exclusive_scan_256(part, s_wave, &before);
+    rank += before;
     const uint32_t local_mask = (local_bits >= 32) ? 0xffffffffu : ((1u << local_bits) - 1u);
 #pragma unroll
     for (int j = 0; j < PX_SORT_ITEMS; ++j) {
@@ -1115,7 +1126,7 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
             memcpy(pack.w, host_words, (size_t) (3 * n_workers + 1) * sizeof(uint64_t));
             k_pack<true, BITS><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, pack, sc.counters, 64, n_workers, m,
                                                                            vocab, local_bits, sc.keys_a, sc.hist, g.chunk,
-                                                                           ctx->d_flags);
+                                                                           ctx->d_flags, sc.hcount);
         } else {
             sort_status = px_upload_words(ctx, ctx->d_words, host_words, 3 * n_workers + 1, sc.counters, 64, stream);
             if (sort_status != PX_OK) return;
@@ -1123,7 +1134,7 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
             unused.w[0] = 0;
             k_pack<false, BITS><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(ctx->d_words, unused, sc.counters, 64, n_workers, m,
                                                                             vocab, local_bits, sc.keys_a, sc.hist, g.chunk,
-                                                                            ctx->d_flags);
+                                                                            ctx->d_flags, sc.hcount);
         }
         uint64_t* src = sc.keys_a;
         uint64_t* dst = sc.keys_b;
@@ -1132,7 +1143,7 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
             if (p > 0) pxr::k_radix_hist<SortWords, BITS><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, g.chunk);
             const int own = g.n_blocks <= PX_OWN_PREFIX_BLOCKS ? g.n_blocks : 0;
             if (!own) pxr::k_radix_prefix<<<(1 << BITS) / 4, 256, 0, stream>>>(sc.hist, g.n_blocks, 1 << BITS, sc.totals);
-            pxr::k_radix_scatter<SortWords, BITS><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, sc.totals, g.chunk, own);
+            pxr::k_radix_scatter<SortWords, BITS><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, sc.hist, sc.totals, g.chunk, own, 0);
             uint64_t* t = src;
             src = dst;
             dst = t;
@@ -1151,7 +1162,6 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
     const int tile_rows = tile_rows_for(m);
     const int64_t n_tiles = (m + tile_rows - 1) / tile_rows;
     const int n_hblocks = (int) ((m + PX_SORT_TILE - 1) / PX_SORT_TILE);
-    k_heads_count<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount);
     uint64_t* rowref = dst;               // the sort's other buffer is free now
     k_heads_emit<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount, tile_rows, ctx->d_words, n_workers, local_bits,
                                                 dim * (int64_t) es, rowref, out_ids, sc.run_start, sc.tile_info,

@@ -116,6 +116,8 @@ extern "C" px_status px_device_status(px_ctx* ctx, void* hip_stream) {
     s = px_check_hip(ctx, hipStreamSynchronize(stream), "status sync");
     if (s != PX_OK) return s;
     uint32_t f = ctx->h_flags[0];
+    if (f & PXF_INTERNAL)
+        return px_fail(ctx, PX_ERR_DEVICE, "a workgroup gave up waiting for another's head count: results of that call are invalid");
     if (f & PXF_BAD_ID)
         return px_fail(ctx, PX_ERR_INDEX_OUT_OF_RANGE, "a row id outside [0, vocab) reached the device");
     if (f & PXF_NOT_UNIQUE)

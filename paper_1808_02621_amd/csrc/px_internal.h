@@ -21,7 +21,7 @@ struct px_ctx {
 // and [buffer pointers] for the dense mean.
 enum { PXW_TOTAL = 3 * PX_MAX_SOURCES + 8 };
 
-enum { PXF_BAD_ID = 1u, PXF_NOT_UNIQUE = 2u };   // bits of d_flags[0]; any set bit stops later updates
+enum { PXF_BAD_ID = 1u, PXF_NOT_UNIQUE = 2u, PXF_INTERNAL = 4u };   // bits of d_flags[0]; any set bit stops later updates
 
 px_status px_fail(px_ctx* ctx, px_status s, const char* fmt, ...);
 px_status px_check_hip(px_ctx* ctx, hipError_t e, const char* what);

@@ -50,6 +50,10 @@ struct ShardPass {
 
 }  // namespace
 
+#ifndef PX_PART_OWN_ROWS
+#define PX_PART_OWN_ROWS 32     // most histogram rows a scatter thread adds up before the prefix launch pays
+#endif
+
 // Scratch of a partition call: the per-block histogram matrix, then the per-bin totals.
 enum : size_t {
     PART_HIST_BYTES = (size_t) PX_SORT_MAX_BLOCKS * 256 * 4,          // a multiple of 256
@@ -66,9 +70,14 @@ static px_status partition_common(px_ctx* ctx, const int64_t* ids, const int64_t
     const px_sort_geom g = px_sort_geometry(cap);
     ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard, out_offsets};
     pxr::k_radix_hist<ShardPass, 8><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.chunk);
-    const int own = g.n_blocks <= PX_OWN_PREFIX_BLOCKS ? g.n_blocks : 0;
+    // Only the first num_shards bins are ever used.  While a thread of the scatter has at most
+    // PX_PART_OWN_ROWS histogram rows to add up for its share of a column, every scatter block adds
+    // the columns up itself and the prefix launch is saved (16 shards: any number of blocks).
+    const int per_bin = PX_SORT_THREADS / num_shards;
+    const bool own = (g.n_blocks + per_bin - 1) / per_bin <= PX_PART_OWN_ROWS;
     if (!own) pxr::k_radix_prefix<<<256 / 4, 256, 0, stream>>>(hist, g.n_blocks, 256, totals);
-    pxr::k_radix_scatter<ShardPass, 8><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, totals, g.chunk, own);
+    pxr::k_radix_scatter<ShardPass, 8><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, totals, g.chunk,
+                                                                                  own ? g.n_blocks : 0, own ? num_shards : 0);
     return px_check_hip(ctx, hipGetLastError(), "partition launch");
 }
 

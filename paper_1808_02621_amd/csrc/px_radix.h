@@ -126,10 +126,14 @@ static __global__ __launch_bounds__(256) void k_radix_prefix(uint32_t* __restric
 }
 
 // own_prefix_blocks > 0: hist holds the raw counts of that many blocks and totals is not read.
+// live_bins > 0 (only with own_prefix_blocks > 0): no digit reaches live_bins, and the columns of
+// the live bins are added up by all threads together (256 / live_bins threads per column), so
+// that a pass with few bins can skip the prefix launch at any number of blocks.
 template <class P, int BITS>
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const uint32_t* __restrict__ hist,
                                                                    const uint32_t* __restrict__ totals,
-                                                                   int64_t chunk, int own_prefix_blocks) {
+                                                                   int64_t chunk, int own_prefix_blocks,
+                                                                   int live_bins) {
     typedef typename P::Item Item;
     enum { BINS = 1 << BITS, BPT = BINS / PX_SORT_THREADS };      // bins per thread: tid*BPT .. tid*BPT + BPT - 1
     __shared__ Item s_items[PX_SORT_TILE];
@@ -148,10 +152,35 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
     uint32_t gpos[BPT];
     {
         uint32_t bin_total[BPT], before[BPT];
+        if (live_bins > 0) {
+            // s_binstart / s_gdst double as the columns' totals / sums over the blocks before this one
+            for (int b = tid; b < BINS; b += PX_SORT_THREADS) {
+                s_binstart[b] = 0u;
+                s_gdst[b] = 0u;
+            }
+            __syncthreads();
+            const int per_bin = PX_SORT_THREADS / live_bins;           // threads per column (live_bins <= 256)
+            if (tid < per_bin * live_bins) {
+                const int bin = tid % live_bins, slot = tid / live_bins;
+                uint32_t tot = 0u, bef = 0u;
+#pragma unroll 8
+                for (int b = slot; b < own_prefix_blocks; b += per_bin) {
+                    const uint32_t c = hist[(size_t) b * BINS + bin];
+                    tot += c;
+                    bef += b < (int) blockIdx.x ? c : 0u;
+                }
+                atomicAdd(&s_binstart[bin], tot);
+                atomicAdd(&s_gdst[bin], bef);
+            }
+            __syncthreads();
+        }
 #pragma unroll
         for (int k = 0; k < BPT; ++k) {
             const int bin = tid * BPT + k;
-            if (own_prefix_blocks > 0) {
+            if (live_bins > 0) {
+                bin_total[k] = s_binstart[bin];
+                before[k] = s_gdst[bin];
+            } else if (own_prefix_blocks > 0) {
                 bin_total[k] = 0u;
                 before[k] = 0u;
 #pragma unroll 8
