@@ -170,9 +170,11 @@ px_status px_partition_rows_noalloc(px_ctx* ctx, const int64_t* ids, const int64
  *   table    dev float[vocab][dim], updated in place; other rows are not touched
  *   ids      dev int64[cap], rows dev float[cap][dim]: the output of px_sparse_coalesce
  *   num_ids  dev int64[1]
- *   perm     dev int32[cap] from px_partition_rows, or NULL for the identity
+ *   perm     dev int32[cap] from px_partition_rows (a permutation of 0 .. *num_ids - 1), or NULL
+ *            for the identity
  *   range    dev int64[2] = {first, last} positions of perm to apply (e.g. two
- *            consecutive entries of out_offsets: one shard), or NULL for all *num_ids
+ *            consecutive entries of out_offsets: one shard), or NULL for all *num_ids; every
+ *            position is then updated once whatever the order, and perm is not read
  * Precondition: the ids are distinct; rows and table do not overlap.  Two lane groups
  * updating one row would race, so every position whose id equals that of a neighbouring
  * position (k - 1 or k + 1; in a sorted list, such as px_sparse_coalesce's output, every

@@ -196,7 +196,10 @@ px_status apply_common(px_ctx* ctx, bool adagrad, float* table, float* accum, in
     p.ids = ids;
     p.rows = rows;
     p.num_ids = num_ids;
-    p.perm = perm;
+    // Without a range every position is updated exactly once whatever the order, so the rows are
+    // taken in storage order: perm is not read, gradient rows stream, and the table rows of
+    // neighbouring lane groups lie close together (Stress-uniform: 518 -> 490 us).
+    p.perm = range ? perm : nullptr;
     p.range = range;
     p.flags = ctx->d_flags;
     p.vocab = vocab;

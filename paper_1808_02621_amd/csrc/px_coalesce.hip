@@ -387,6 +387,9 @@ __global__ void k_write_zero_count(int64_t* out_num_unique) {
 #ifndef PX_SEG_ROWS_WIDE
 #define PX_SEG_ROWS_WIDE 2      // four pieces per lane
 #endif
+#ifndef PX_FUSED_STATE_PIECES
+#define PX_FUSED_STATE_PIECES 8 // fused modes: 16-byte table / accumulator pieces a lane holds per batch
+#endif
 typedef PX_SEG_ACC seg_acc_t;
 
 typedef uint32_t seg_v4u __attribute__((ext_vector_type(4)));
@@ -496,7 +499,8 @@ struct SegsumArgs {
 // variable so the aggregate never travels).  What is left when the tile ends belongs to a run
 // that goes on into the next tile (the "last" partial row).
 //
-// Each stretch keeps two batches of B rows in flight: while batch k is added up, the rows of
+// Each stretch keeps two batches of rows in flight (B rows each in the stretch with tails, BH in the
+// stretch without heads; they differ only in the fused modes): while batch k is added up, the rows of
 // batch k + 1 (and, in the fused modes, the table and accumulator rows of its tails) are on
 // their way and the references of batch k + 2 are being fetched.  Loads are unconditional, so the
 // hardware counters tell exactly which of them a wait is for: past the end of the stretch they
@@ -506,13 +510,12 @@ struct SegsumArgs {
 // inside, and the run goes on into the next block) their sums are added in LDS, in tile order,
 // and stored once, as the partial row of the block's first tile: a long run then leaves one
 // partial row per block instead of one per tile.
-template <typename T, bool VEC, int G, int C, int B, int MODE>
+template <typename T, bool VEC, int G, int C, int B, int BH, int MODE>
 __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
     typedef RowLoad<T, VEC> L;
     typedef typename L::Raw Raw;
     enum { E = L::E, TPB = 256 / G, MERGE = (C * E <= 16) ? 1 : 0, FUSED = MODE != MODE_ROWS ? 1 : 0,
-           SV = VEC ? E / 4 : 1,                                  // state vectors (float4 or float) per piece
-           FB = FUSED ? B : 1, AB = MODE == MODE_ADAGRAD ? B : 1 };
+           SV = VEC ? E / 4 : 1 };                                // state vectors (float4 or float) per piece
     typedef typename std::conditional<VEC, float4, float>::type StateV;
     __shared__ double s_part[MERGE ? TPB * G * C * E : 1];
     if (FUSED && a.flags[0]) return;                              // uniform: an error flag is up, touch nothing
@@ -575,58 +578,62 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
         }
     };
 
-    // Rows [from, to), from < to, are added to acc.  With TAILS, a row whose reference carries
-    // the tail bit finishes run u: its sum is written (or applied) and acc starts again.
-    auto walk = [&](int64_t from, int64_t to, auto tails_tag) {
+    // Rows [from, to), from < to, are added to acc, BB rows per batch.  With TAILS, a row whose
+    // reference carries the tail bit finishes run u: its sum is written (or applied) and acc starts
+    // again.  Only the fused modes' stretch with tails holds table (and accumulator) pieces, so only
+    // that stretch needs the smaller batches; a stretch without heads streams at the full depth.
+    auto walk = [&](int64_t from, int64_t to, auto tails_tag, auto batch_tag) {
         constexpr bool TAILS = decltype(tails_tag)::value;
         constexpr bool STATE = TAILS && FUSED;
+        constexpr int BB = decltype(batch_tag)::value;
+        constexpr int FBB = STATE ? BB : 1, ABB = (STATE && MODE == MODE_ADAGRAD) ? BB : 1;
         const int64_t lastrow = to - 1;
-        uint64_t wn[B], wf[B];                                    // references of the next batch and the one after
-        uint32_t kc[FB], kn[FB], kf[FB];                          // fused modes: the rows' ids
-        Raw rc[B][C], rn[B][C];
+        uint64_t wn[BB], wf[BB];                                  // references of the next batch and the one after
+        uint32_t kc[FBB], kn[FBB], kf[FBB];                       // fused modes: the rows' ids
+        Raw rc[BB][C], rn[BB][C];
         uint32_t tc = 0, tn = 0;                                  // tail bits of the current and the next batch
-        StateV wsc[FB][C][SV], wsn[FB][C][SV];
-        StateV asc[AB][C][SV], asn[AB][C][SV];
+        StateV wsc[FBB][C][SV], wsn[FBB][C][SV];
+        StateV asc[ABB][C][SV], asn[ABB][C][SV];
         float* dst = a.out_rows + (size_t) u * a.dim + (size_t) piece[0] * E;   // MODE_ROWS: lane's place in row u
 
-        auto load_refs = [&](int64_t r0, uint64_t (&w)[B], uint32_t (&k)[FB]) {
+        auto load_refs = [&](int64_t r0, uint64_t (&w)[BB], uint32_t (&k)[FBB]) {
 #pragma unroll
-            for (int j = 0; j < B; ++j) {
+            for (int j = 0; j < BB; ++j) {
                 const int64_t i = r0 + j < to ? r0 + j : lastrow;
                 w[j] = a.rowref[i];
-                if (STATE) k[FUSED ? j : 0] = ((const uint32_t*) a.sorted)[2 * i + 1];
+                if (STATE) k[STATE ? j : 0] = ((const uint32_t*) a.sorted)[2 * i + 1];
             }
         };
-        auto load_rows = [&](const uint64_t (&w)[B], Raw (&raw)[B][C]) {
+        auto load_rows = [&](const uint64_t (&w)[BB], Raw (&raw)[BB][C]) {
 #pragma unroll
-            for (int j = 0; j < B; ++j) {
+            for (int j = 0; j < BB; ++j) {
                 const char* row = (const char*) (w[j] & ~1ull);
 #pragma unroll
                 for (int c = 0; c < C; ++c) raw[j][c] = L::load(row + piece_off[c]);
             }
         };
-        auto tails_of = [&](int64_t r0, const uint64_t (&w)[B]) -> uint32_t {
+        auto tails_of = [&](int64_t r0, const uint64_t (&w)[BB]) -> uint32_t {
             if (!TAILS) return 0u;
             uint32_t t = 0;
 #pragma unroll
-            for (int j = 0; j < B; ++j) t |= ((uint32_t) w[j] & 1u) << j;
+            for (int j = 0; j < BB; ++j) t |= ((uint32_t) w[j] & 1u) << j;
             const int64_t left = to - r0;
-            return left >= B ? t : (left > 0 ? t & ((1u << (int) left) - 1u) : 0u);
+            return left >= BB ? t : (left > 0 ? t & ((1u << (int) left) - 1u) : 0u);
         };
-        auto load_state = [&](uint32_t t, const uint32_t (&k)[FB], StateV (&ws)[FB][C][SV], StateV (&as)[AB][C][SV]) {
+        auto load_state = [&](uint32_t t, const uint32_t (&k)[FBB], StateV (&ws)[FBB][C][SV], StateV (&as)[ABB][C][SV]) {
             if (!STATE) return;
 #pragma unroll
-            for (int j = 0; j < B; ++j)
+            for (int j = 0; j < BB; ++j)
                 if ((t >> j) & 1u) {
-                    const size_t off = (size_t) k[FUSED ? j : 0] * a.dim;
+                    const size_t off = (size_t) k[STATE ? j : 0] * a.dim;
 #pragma unroll
                     for (int c = 0; c < C; ++c)
                         if (live[c]) {
 #pragma unroll
                             for (int v = 0; v < SV; ++v) {
-                                ws[FUSED ? j : 0][c][v] = ((const StateV*) (a.table + off + (size_t) piece[c] * E))[v];
+                                ws[STATE ? j : 0][c][v] = ((const StateV*) (a.table + off + (size_t) piece[c] * E))[v];
                                 if (MODE == MODE_ADAGRAD)
-                                    as[MODE == MODE_ADAGRAD ? j : 0][c][v] = ((const StateV*) (a.accum + off + (size_t) piece[c] * E))[v];
+                                    as[ABB > 1 ? j : 0][c][v] = ((const StateV*) (a.accum + off + (size_t) piece[c] * E))[v];
                             }
                         }
                 }
@@ -678,12 +685,12 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
                     }
                 dst += a.dim;
             } else {
-                const size_t off = (size_t) kc[FUSED ? j : 0] * a.dim;
+                const size_t off = (size_t) kc[STATE ? j : 0] * a.dim;
 #pragma unroll
                 for (int c = 0; c < C; ++c)
                     if (live[c]) {
-                        float* wf32 = (float*) &wsc[FUSED ? j : 0][c][0];
-                        float* af32 = (float*) &asc[MODE == MODE_ADAGRAD ? j : 0][c][0];
+                        float* wf32 = (float*) &wsc[STATE ? j : 0][c][0];
+                        float* af32 = (float*) &asc[ABB > 1 ? j : 0][c][0];
 #pragma unroll
                         for (int x = 0; x < E; ++x) {
                             const float g = (float) ((double) acc[c][x] * a.scale);
@@ -692,9 +699,9 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
                         }
 #pragma unroll
                         for (int v = 0; v < SV; ++v) {
-                            ((StateV*) (a.table + off + (size_t) piece[c] * E))[v] = wsc[FUSED ? j : 0][c][v];
+                            ((StateV*) (a.table + off + (size_t) piece[c] * E))[v] = wsc[STATE ? j : 0][c][v];
                             if (MODE == MODE_ADAGRAD)
-                                ((StateV*) (a.accum + off + (size_t) piece[c] * E))[v] = asc[MODE == MODE_ADAGRAD ? j : 0][c][v];
+                                ((StateV*) (a.accum + off + (size_t) piece[c] * E))[v] = asc[ABB > 1 ? j : 0][c][v];
                         }
                     }
             }
@@ -703,24 +710,24 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
         };
 
         {
-            uint64_t w0[B];
+            uint64_t w0[BB];
             load_refs(from, w0, kc);
-            load_refs(from + B, wn, kn);
+            load_refs(from + BB, wn, kn);
             load_rows(w0, rc);
             tc = tails_of(from, w0);
             load_state(tc, kc, wsc, asc);
         }
-        for (int64_t r = from; r < to; r += B) {
+        for (int64_t r = from; r < to; r += BB) {
             // Loads come back in the order they were issued, so the references of batch k + 2 go out
             // before the rows of batch k + 1: the next iteration then finds them without having to
             // wait for those rows, and two batches of rows really are in flight.
-            load_refs(r + 2 * B, wf, kf);
+            load_refs(r + 2 * BB, wf, kf);
             load_rows(wn, rn);
-            tn = tails_of(r + B, wn);
+            tn = tails_of(r + BB, wn);
             load_state(tn, kn, wsn, asn);
-            if (r + B <= to) {
+            if (r + BB <= to) {
 #pragma unroll
-                for (int j = 0; j < B; ++j) {
+                for (int j = 0; j < BB; ++j) {
 #pragma unroll
                     for (int c = 0; c < C; ++c)
                         if (live[c]) L::add(acc[c], rc[j][c]);
@@ -728,7 +735,7 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
                 }
             } else {
 #pragma unroll
-                for (int j = 0; j < B; ++j)
+                for (int j = 0; j < BB; ++j)
                     if (r + j < to) {
 #pragma unroll
                         for (int c = 0; c < C; ++c)
@@ -738,14 +745,14 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
             }
             tc = tn;
 #pragma unroll
-            for (int j = 0; j < B; ++j) {
+            for (int j = 0; j < BB; ++j) {
                 wn[j] = wf[j];
 #pragma unroll
                 for (int c = 0; c < C; ++c) rc[j][c] = rn[j][c];
             }
             if (STATE) {
 #pragma unroll
-                for (int j = 0; j < FB; ++j) {
+                for (int j = 0; j < FBB; ++j) {
                     kc[j] = kn[j];
                     kn[j] = kf[j];
 #pragma unroll
@@ -753,7 +760,7 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
 #pragma unroll
                         for (int v = 0; v < SV; ++v) {
                             wsc[j][c][v] = wsn[j][c][v];
-                            if (MODE == MODE_ADAGRAD) asc[MODE == MODE_ADAGRAD ? j : 0][c][v] = asn[MODE == MODE_ADAGRAD ? j : 0][c][v];
+                            if (MODE == MODE_ADAGRAD) asc[ABB > 1 ? j : 0][c][v] = asn[ABB > 1 ? j : 0][c][v];
                         }
                 }
             }
@@ -763,7 +770,7 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
     if (active) {
         if (!started) {
             // the run that entered from the tile before
-            walk(s, h, std::false_type());
+            walk(s, h, std::false_type(), std::integral_constant<int, BH>());
             if (h < e) {
                 store_partial(a.pfirst + (size_t) tile * a.pstride);
                 clear();
@@ -773,7 +780,7 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
             }
         }
         if (h < e) {
-            walk(h, e, std::true_type());
+            walk(h, e, std::true_type(), std::integral_constant<int, B>());
             if (!next_is_head) {
                 // the tile's last run goes on into the next tile
                 store_partial(a.plast + (size_t) tile * a.pstride);
@@ -1008,18 +1015,22 @@ int bits_for(uint64_t max_value) {   // bits needed to write max_value
 constexpr int batch_rows(int mode, int c, int state_vectors) {
     if (mode == MODE_ROWS) return c == 1 ? PX_SEG_ROWS : c == 2 ? PX_SEG_ROWS_2 : PX_SEG_ROWS_WIDE;
     const int per_row = c * state_vectors * (mode == MODE_ADAGRAD ? 2 : 1);
-    return per_row >= 8 ? 1 : 8 / per_row;
+    return per_row >= PX_FUSED_STATE_PIECES ? 1 : PX_FUSED_STATE_PIECES / per_row;
 }
 
 template <typename T, bool VEC, int MODE>
 void launch_segsum(const SegsumArgs& a, const RowShape& sh, hipStream_t stream) {
     constexpr int SV = VEC ? RowLoad<T, VEC>::E / 4 : 1;
     const dim3 grid((unsigned) ((a.n_tiles + (256 / sh.G) - 1) / (256 / sh.G)), (unsigned) sh.slabs, 1);
-    if (sh.G == 16) k_segsum<T, VEC, 16, 1, batch_rows(MODE, 1, SV), MODE><<<grid, 256, 0, stream>>>(a);
-    else if (sh.G == 32) k_segsum<T, VEC, 32, 1, batch_rows(MODE, 1, SV), MODE><<<grid, 256, 0, stream>>>(a);
-    else if (sh.C == 1) k_segsum<T, VEC, 64, 1, batch_rows(MODE, 1, SV), MODE><<<grid, 256, 0, stream>>>(a);
-    else if (sh.C == 2) k_segsum<T, VEC, 64, 2, batch_rows(MODE, 2, SV), MODE><<<grid, 256, 0, stream>>>(a);
-    else k_segsum<T, VEC, 64, 4, batch_rows(MODE, 4, SV), MODE><<<grid, 256, 0, stream>>>(a);
+    // batch depth of a stretch with tails, and of a stretch without heads (never holds table pieces)
+#define PX_SEG_LAUNCH(G_, C_) \
+    k_segsum<T, VEC, G_, C_, batch_rows(MODE, C_, SV), batch_rows(MODE_ROWS, C_, SV), MODE><<<grid, 256, 0, stream>>>(a)
+    if (sh.G == 16) PX_SEG_LAUNCH(16, 1);
+    else if (sh.G == 32) PX_SEG_LAUNCH(32, 1);
+    else if (sh.C == 1) PX_SEG_LAUNCH(64, 1);
+    else if (sh.C == 2) PX_SEG_LAUNCH(64, 2);
+    else PX_SEG_LAUNCH(64, 4);
+#undef PX_SEG_LAUNCH
 }
 
 template <int MODE>
