@@ -33,8 +33,8 @@ HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E peak
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="nmt_like")
     ap.add_argument("--no-others", action="store_true", help="skip the brief runs of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -295,6 +295,40 @@ def per_call(torch, dw, steps, warmup):
     return out
 
 
+# ------------------------------------------------------- two-level aggregation
+
+def two_level_timing(torch, runner, ctx, b0, w, group, iters=10, warmup=2):
+    """Local aggregation per group of `group` workers, then global aggregation of the groups' results
+    (Sec. 4.3), against one coalesce of all workers.  Every buffer is allocated before the timed
+    regions.  The stages are timed apart, each in a loop of its own so that the device queue stays
+    full and an event pair brackets device time only: the group coalesces, the second-level
+    coalesce (on the counts read once), the one-level coalesce; the read-back of the groups' counts
+    is a synchronisation and is timed with the host clock."""
+    t = runner.two_level_buffers(b0.idx, b0.val, w.dim, w.vocab, group)
+    runner.two_level_first(ctx, t)
+    read_us = []
+    for _ in range(iters):
+        runner.two_level_first(ctx, t)
+        torch.cuda.synchronize()
+        h0 = time.perf_counter()
+        counts = runner.two_level_read_counts(t)
+        read_us.append((time.perf_counter() - h0) * 1e6)
+    event_timed(torch, lambda: runner.two_level_first(ctx, t), iters, warmup)
+    first = event_timed.last_median
+    event_timed(torch, lambda: runner.two_level_second(ctx, t, counts), iters, warmup)
+    second = event_timed.last_median
+    event_timed(torch, lambda: runner.coalesce(ctx, b0), iters, warmup)
+    one = event_timed.last_median
+    assert int(t.second.out_num.item()) == int(b0.out_num.item())
+    return {
+        "what": "coalesce per group of %d workers (%d calls), read the %d counts back, coalesce the groups' results; "
+                "all buffers allocated beforehand; medians of %d" % (group, len(t.firsts), len(t.firsts), iters),
+        "first_level_us": first * 1e6, "count_readback_us": float(np.median(read_us)), "second_level_us": second * 1e6,
+        "two_level_us": first * 1e6 + float(np.median(read_us)) + second * 1e6, "one_level_us": one * 1e6,
+        "input_rows": w.total_rows, "rows_into_second_level": int(sum(counts)), "unique_rows": int(b0.out_num.item()),
+    }
+
+
 # ------------------------------------------------------------- sparsity sweep
 
 SWEEP_VOCAB = 50_000
@@ -416,10 +450,12 @@ def main():
     sp_bytes, dn_bytes = dw.algorithmic_bytes()
 
     # the timed region: exactly K steps, with an event pair around the dominant kernel's call
-    dense_pairs = []
+    dense_pairs, step_pairs = [], []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
+        s0 = torch.cuda.Event(enable_timing=True)
+        s0.record()
         dw.sparse()
         if dw.dense:
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -427,9 +463,13 @@ def main():
             dw.dense_mean()
             b.record()
             dense_pairs.append((a, b))
+        s1 = torch.cuda.Event(enable_timing=True)
+        s1.record()
+        step_pairs.append((s0, s1))
         dw.step_no += 1
     torch.cuda.synchronize()
     sec_per_step = (time.perf_counter() - t0) / args.steps
+    step_ms = [a.elapsed_time(b) for a, b in step_pairs]
 
     rows_per_step = w.n_tables * w.total_rows
     result = {
@@ -438,6 +478,8 @@ def main():
         "unit": "rows/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec_per_step * 1e3,
+        # the same K steps, each bracketed by an event pair on the stream: median and minimum
+        "ms_per_step_median": float(np.median(step_ms)), "ms_per_step_min": float(np.min(step_ms)),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64",      # sums are formed in double; inputs are bf16 or f32, tables and outputs float32
         "data": "synthetic",
@@ -485,6 +527,14 @@ def main():
         "achieved_gbps_unfused_bytes": sp_bytes / fused_avg / 1e9,
         "frac_unfused_bytes": sp_bytes / fused_avg / 1e9 / HBM_PEAK_GBPS,
         "rows_per_s": rows_per_step / fused_avg,
+    }
+    fused_med = event_timed.last_median
+    sep_med = result["sparse_chain"]["median_us"] * 1e-6
+    result["sparse_chain_best"] = {
+        "what": "the faster of the separate calls and the fused entry points on this workload (medians); the fused "
+                "path saves 2*U*D*4 bytes and pays unless rows are narrow and heavily duplicated",
+        "path": "fused" if fused_med < sep_med else "separate", "median_us": min(fused_med, sep_med) * 1e6,
+        "frac_unfused_bytes": sp_bytes / min(fused_med, sep_med) / 1e9 / HBM_PEAK_GBPS,
     }
     # the same step with the independent pieces on their own streams: reported beside the headline,
     # which stays on one stream so that every kernel's duration is its own
@@ -540,29 +590,24 @@ def main():
                 odw.step_no += 1
 
             s_avg, s_min = event_timed(torch, sparse_rot, 20, 4)
+            s_med = event_timed.last_median
             f_avg, f_min = event_timed(torch, fused_rot, 20, 4)
-            entry = {"unique_rows": odw.unique_counts(), "sparse_calls": per_call(torch, odw, 10, 2),
+            f_med = event_timed.last_median
+            entry = {"sparse_median_us": s_med * 1e6, "fused_median_us": f_med * 1e6,
+                     "best_path": "fused" if f_med < s_med else "separate",
+                     "best_frac_unfused_bytes": obytes / min(f_med, s_med) / 1e9 / HBM_PEAK_GBPS,
+                     "input_rows": ow.n_tables * ow.total_rows}
+            entry.update({"unique_rows": odw.unique_counts(), "sparse_calls": per_call(torch, odw, 10, 2),
                      "sparse_avg_us": s_avg * 1e6, "sparse_min_us": s_min * 1e6,
                      "sparse_gbps": obytes / s_avg / 1e9, "sparse_frac": obytes / s_avg / 1e9 / HBM_PEAK_GBPS,
                      "rows_per_s": ow.n_tables * ow.total_rows / s_avg,
-                     "fused_avg_us": f_avg * 1e6, "fused_frac_unfused_bytes": obytes / f_avg / 1e9 / HBM_PEAK_GBPS}
+                     "fused_avg_us": f_avg * 1e6, "fused_frac_unfused_bytes": obytes / f_avg / 1e9 / HBM_PEAK_GBPS})
             if name == "large_vocab_lm":
                 entry["partition_search"] = partition_search(torch, px, odw)
-                b0 = odw.bufs[0][0]
-
-                def two_level(b0=b0, ow=ow):
-                    odw.runner.two_level_coalesce(ctx, b0.idx, b0.val, ow.dim, ow.vocab, 6)
-
-                def one_level(b0=b0):
-                    odw.runner.coalesce(ctx, b0)
-
-                t2, _ = event_timed(torch, two_level, 10, 2)
-                t1, _ = event_timed(torch, one_level, 10, 2)
                 entry["sparsity_sweep"] = sparsity_sweep(torch, px, ctx, ow)
-                entry["two_level_aggregation"] = {
-                    "what": "coalesce per group of 6 workers, read the 8 counts back, coalesce the 8 results "
-                            "(allocations included) vs one coalesce of all 48",
-                    "two_level_us": t2 * 1e6, "one_level_us": t1 * 1e6}
+                entry["two_level_aggregation"] = two_level_timing(torch, odw.runner, ctx, odw.bufs[0][0], ow, 6)
+            if name == "stress_zipf":
+                entry["two_level_aggregation"] = two_level_timing(torch, odw.runner, ctx, odw.bufs[0][0], ow, 8)
             odw.pull_setup()
             p_avg, _ = event_timed(torch, odw.pull, 10, 2)
             entry.update({"pull_avg_us": p_avg * 1e6, "pull_frac": odw.pull_bytes() / p_avg / 1e9 / HBM_PEAK_GBPS})

@@ -112,19 +112,53 @@ def fused_step(ctx: px.Context, b: SparseBuffers, table: torch.Tensor, accum: Op
     partition(ctx, b, stream)
 
 
+@dataclasses.dataclass
+class TwoLevelBuffers:
+    """Everything two-level aggregation touches, allocated once: one SparseBuffers per group of workers
+    and one for the second level, sized for the case that no group combines anything."""
+
+    firsts: List[SparseBuffers]
+    second: SparseBuffers
+    counts: torch.Tensor          # the groups' distinct-row counts, gathered for one read-back
+
+
+def two_level_buffers(idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], dim: int, vocab: int,
+                      group: int, device="cuda") -> TwoLevelBuffers:
+    firsts = [sparse_buffers(idx[g0:g0 + group], val[g0:g0 + group], dim, vocab, 1, px.PX_HASH_MOD, device)
+              for g0 in range(0, len(idx), group)]
+    # the second level reads the first level's outputs in place; its own outputs and scratch are sized
+    # for all of them being full
+    second = sparse_buffers([b.out_ids for b in firsts], [b.out_rows for b in firsts], dim, vocab, 1,
+                            px.PX_HASH_MOD, device)
+    return TwoLevelBuffers(firsts, second, torch.zeros(len(firsts), dtype=torch.int64, device=device))
+
+
+def two_level_first(ctx: px.Context, t: TwoLevelBuffers, stream=None) -> None:
+    """Local aggregation: one coalesce per group of workers (Parallax Sec. 4.3), enqueued back to back."""
+    for b in t.firsts:
+        coalesce(ctx, b, 1.0, stream)
+
+
+def two_level_read_counts(t: TwoLevelBuffers) -> List[int]:
+    """The one synchronisation: the second call takes its row counts from the host."""
+    torch.stack([b.out_num[0] for b in t.firsts], out=t.counts)
+    return t.counts.cpu().tolist()
+
+
+def two_level_second(ctx: px.Context, t: TwoLevelBuffers, counts: Sequence[int], stream=None) -> None:
+    """Global aggregation of the groups' results (views of the first level's outputs, nothing is copied)."""
+    t.second.idx = [b.out_ids[:n] for b, n in zip(t.firsts, counts)]
+    t.second.val = [b.out_rows[:n] for b, n in zip(t.firsts, counts)]
+    coalesce(ctx, t.second, 1.0, stream)
+
+
 def two_level_coalesce(ctx: px.Context, idx: Sequence[torch.Tensor], val: Sequence[torch.Tensor], dim: int,
                        vocab: int, group: int, stream=None):
     """Aggregation in two levels (Parallax Sec. 4.3): first among the `group` workers of each machine,
     then across machines.  Returns the second level's SparseBuffers (ids, rows, count) and the list
     of first-level buffers.  The first-level counts are read back to the host in between (one
     synchronisation), because the second call takes its row counts from the host."""
-    firsts = []
-    for g0 in range(0, len(idx), group):
-        b = sparse_buffers(idx[g0:g0 + group], val[g0:g0 + group], dim, vocab, 1, px.PX_HASH_MOD)
-        coalesce(ctx, b, 1.0, stream)
-        firsts.append(b)
-    counts = torch.cat([b.out_num for b in firsts]).cpu().tolist()
-    second = sparse_buffers([b.out_ids[:n] for b, n in zip(firsts, counts)],
-                            [b.out_rows[:n] for b, n in zip(firsts, counts)], dim, vocab, 1, px.PX_HASH_MOD)
-    coalesce(ctx, second, 1.0, stream)
-    return second, firsts
+    t = two_level_buffers(idx, val, dim, vocab, group)
+    two_level_first(ctx, t, stream)
+    two_level_second(ctx, t, two_level_read_counts(t), stream)
+    return t.second, t.firsts
