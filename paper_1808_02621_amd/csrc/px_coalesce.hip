@@ -186,6 +186,19 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__
     if (end > m) end = m;
     // the head-ranking kernel publishes one word per PX_SORT_TILE rows: clear those of this chunk
     for (int64_t h = begin / PX_SORT_TILE + tid; h * PX_SORT_TILE < end; h += PX_SORT_THREADS) hpub[h] = 0u;
+    // the chunk spans few workers: look for a row's worker only among those
+    auto worker_of = [&](int64_t p, int lo, int hi) {               // s_prefix[lo] <= p < s_prefix[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if ((int64_t) s_prefix[mid] <= p) lo = mid; else hi = mid;
+        }
+        return lo;
+    };
+    int w_first = 0, w_last = 0;
+    if (begin < end) {
+        w_first = worker_of(begin, 0, n_workers);
+        w_last = worker_of(end - 1, w_first, n_workers);
+    }
     // PX_SORT_ITEMS rows per thread at a time: their ids are requested together
     for (int64_t p0 = begin + tid; p0 < end; p0 += (int64_t) PX_SORT_THREADS * PX_SORT_ITEMS) {
         uint32_t local[PX_SORT_ITEMS];
@@ -198,11 +211,7 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_pack(uint64_t* __restrict__
             src[j] = 0;
             local[j] = 0u;
             if (p < end) {
-                int lo = 0, hi = n_workers;             // s_prefix[lo] <= p < s_prefix[hi]
-                while (hi - lo > 1) {
-                    int mid = (lo + hi) >> 1;
-                    if ((int64_t) s_prefix[mid] <= p) lo = mid; else hi = mid;
-                }
+                const int lo = worker_of(p, w_first, w_last + 1);
                 src[j] = lo;
                 local[j] = (uint32_t) (p - (int64_t) s_prefix[lo]);
                 const PX_GLOBAL int64_t* ids = (const PX_GLOBAL int64_t*) (CARRIED ? s_idx[lo] : words[lo]);
@@ -313,6 +322,20 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
     uint32_t rank = pxr::block_exclusive_scan_256(cnt, s_wave, &block_total);   // syncs
     if (tid == 0)
         __hip_atomic_store(&hpub[blockIdx.x], 0x80000000u | block_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t local_mask = (local_bits >= 32) ? 0xffffffffu : ((1u << local_bits) - 1u);
+    // row references, consecutive lanes on consecutive rows so that the stores coalesce; they need no
+    // rank, so they are written while the other blocks' counts are on their way
+#pragma unroll
+    for (int j = 0; j < PX_SORT_ITEMS; ++j) {
+        const int64_t i = (int64_t) block_base + j * 256 + tid;
+        if (i < m) {
+            const uint64_t wi = sorted[i];
+            const bool tail = i + 1 >= m || key_of(sorted[i + 1]) != key_of(wi);
+            const uint32_t payload = (uint32_t) wi;
+            const uint32_t worker = (local_bits >= 32) ? 0u : (payload >> local_bits);
+            rowref[i] = (s_vbase[worker] + (uint64_t) (payload & local_mask) * (uint64_t) row_bytes) | (tail ? 1ull : 0ull);
+        }
+    }
     // heads in all blocks before this one
     uint32_t part = 0;
     for (int b = tid; b < (int) blockIdx.x; b += 256) {
@@ -330,7 +353,6 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
     uint32_t before;
     pxr::block_exclusive_scan_256(part, s_wave, &before);
     rank += before;
-    const uint32_t local_mask = (local_bits >= 32) ? 0xffffffffu : ((1u << local_bits) - 1u);
 #pragma unroll
     for (int j = 0; j < PX_SORT_ITEMS; ++j) {
         const int64_t i = base + j;
@@ -354,18 +376,6 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
         const uint32_t u = before + block_total;
         run_start[u] = (uint32_t) m;
         out_num_unique[0] = (flags[0] & PXF_BAD_ID) ? 0 : (int64_t) u;
-    }
-    // row references, consecutive lanes on consecutive rows so that the stores coalesce
-#pragma unroll
-    for (int j = 0; j < PX_SORT_ITEMS; ++j) {
-        const int64_t i = (int64_t) block_base + j * 256 + tid;
-        if (i < m) {
-            const uint64_t wi = sorted[i];
-            const bool tail = i + 1 >= m || key_of(sorted[i + 1]) != key_of(wi);
-            const uint32_t payload = (uint32_t) wi;
-            const uint32_t worker = (local_bits >= 32) ? 0u : (payload >> local_bits);
-            rowref[i] = (s_vbase[worker] + (uint64_t) (payload & local_mask) * (uint64_t) row_bytes) | (tail ? 1ull : 0ull);
-        }
     }
 }
 

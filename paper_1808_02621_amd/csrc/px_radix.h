@@ -148,6 +148,30 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
     const int wave = tid >> 6;
     const uint64_t below = lanes_below();
 
+    const int64_t n = p.count();
+    const int64_t begin = (int64_t) blockIdx.x * chunk;
+    int64_t end = begin + chunk;
+    if (end > n) end = n;
+
+    // The items of a tile are requested together; those of the first tile before anything else, so
+    // that they travel while the block works out where its bins start.
+    Item it[PX_SORT_ITEMS];
+    uint32_t dg[PX_SORT_ITEMS];
+    auto load_tile = [&](int64_t tile0) {
+        const int64_t left = end - tile0;
+#pragma unroll
+        for (int i = 0; i < PX_SORT_ITEMS; ++i) {
+            const int local = wave * (64 * PX_SORT_ITEMS) + i * 64 + (int) lane;
+            it[i] = Item(0);
+            dg[i] = 0u;
+            if ((int64_t) local < left) {
+                it[i] = p.load(tile0 + local);
+                dg[i] = p.digit(it[i], tile0 + local);
+            }
+        }
+    };
+    load_tile(begin);
+
     // Where this thread's bins start in the output, for this block.
     uint32_t gpos[BPT];
     {
@@ -207,11 +231,6 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
         }
     }
 
-    const int64_t n = p.count();
-    const int64_t begin = (int64_t) blockIdx.x * chunk;
-    int64_t end = begin + chunk;
-    if (end > n) end = n;
-
     for (int64_t tile0 = begin; tile0 < end; tile0 += PX_SORT_TILE) {
         const int tcount = (int) ((end - tile0) < PX_SORT_TILE ? (end - tile0) : PX_SORT_TILE);
 #pragma unroll
@@ -220,18 +239,13 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
             for (int k = 0; k < BPT; ++k) s_wcnt[w][tid * BPT + k] = 0u;
         __syncthreads();
 
-        Item it[PX_SORT_ITEMS];
-        uint32_t dg[PX_SORT_ITEMS], rk[PX_SORT_ITEMS];
+        if (tile0 != begin) load_tile(tile0);
+        uint32_t rk[PX_SORT_ITEMS];
 #pragma unroll
         for (int i = 0; i < PX_SORT_ITEMS; ++i) {
             const int local = wave * (64 * PX_SORT_ITEMS) + i * 64 + (int) lane;
             const bool valid = local < tcount;
-            Item v = Item(0);
-            uint32_t d = 0;
-            if (valid) {
-                v = p.load(tile0 + local);
-                d = p.digit(v, tile0 + local);
-            }
+            const uint32_t d = dg[i];
             uint64_t same = __ballot(valid);
 #pragma unroll
             for (int bit = 0; bit < BITS; ++bit) {
@@ -247,8 +261,6 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
             }
             const int leader = valid ? (__ffsll((unsigned long long) same) - 1) : (int) lane;
             old = __shfl(old, leader);
-            it[i] = v;
-            dg[i] = d;
             rk[i] = old + r;
         }
         __syncthreads();
