@@ -65,6 +65,8 @@ extern "C" px_status px_create(px_ctx** out, int device) {
     if (e == hipSuccess) e = hipMalloc((void**) &ctx->d_flags, 64 * sizeof(uint32_t));
     if (e == hipSuccess) e = hipHostMalloc((void**) &ctx->h_flags, 64 * sizeof(uint32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipMemset(ctx->d_flags, 0, 64 * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc((void**) &ctx->d_part_pub, PX_PART_PUB_WORDS * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMemset(ctx->d_part_pub, 0, PX_PART_PUB_WORDS * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e == hipSuccess && px_partition_noalloc_setup(ctx) != PX_OK) e = hipErrorInvalidSymbol;
     (void) hipSetDevice(prev);
@@ -80,6 +82,7 @@ extern "C" px_status px_destroy(px_ctx* ctx) {
     if (!ctx) return PX_OK;
     if (ctx->d_words) (void) hipFree(ctx->d_words);
     if (ctx->d_flags) (void) hipFree(ctx->d_flags);
+    if (ctx->d_part_pub) (void) hipFree(ctx->d_part_pub);
     if (ctx->h_flags) (void) hipHostFree(ctx->h_flags);
     free(ctx);
     return PX_OK;

@@ -14,12 +14,16 @@ struct px_ctx {
     uint32_t* d_flags;   // device: [0] sticky error flag
     uint32_t* h_flags;   // pinned host mirror for px_device_status
     void* part_scratch;  // device address of the partition's built-in scratch on this GPU (not owned)
+    unsigned long long* d_part_pub;   // device: PX_PART_PUB_WORDS words, shard counts published by a single-launch partition
+    uint32_t part_call;  // number of the last single-launch partition on this context (tags the published words)
     char err[512];
 };
 
 // d_words holds, per call, [idx pointers | value pointers | row prefix (n + 1)] for coalesce
 // and [buffer pointers] for the dense mean.
 enum { PXW_TOTAL = 3 * PX_MAX_SOURCES + 8 };
+
+enum { PX_PART_PUB_WORDS = 2048 };   // most (blocks x shards) of a single-launch partition: 8 words per thread to read
 
 enum { PXF_BAD_ID = 1u, PXF_NOT_UNIQUE = 2u, PXF_INTERNAL = 4u };   // bits of d_flags[0]; any set bit stops later updates
 

@@ -23,6 +23,9 @@ struct ShardPass {
     int32_t* out_perm;
     int32_t* out_shard;
     int64_t* out_offsets;
+    unsigned long long* pub_words;         // single-launch mode: the blocks' published shard counts
+    uint32_t call_no;                      //   and the number of this call
+    uint32_t* flags;                       //   the context's error flags
 
     __device__ int64_t count() const {
         int64_t n = num[0];
@@ -30,6 +33,9 @@ struct ShardPass {
         if (n > cap) n = cap;
         return n;
     }
+    __device__ unsigned long long* pub() const { return pub_words; }
+    __device__ uint32_t call_number() const { return call_no; }
+    __device__ void fail() const { atomicOr(flags, (uint32_t) PXF_INTERNAL); }
     __device__ Item load(int64_t i) const { return (uint32_t) i; }
     __device__ uint32_t digit(Item, int64_t i) const {
         uint64_t h = (uint64_t) ids[i];
@@ -37,6 +43,7 @@ struct ShardPass {
         if ((n_shards & (n_shards - 1u)) == 0u) return (uint32_t) h & (n_shards - 1u);
         return (uint32_t) (h % (uint64_t) n_shards);
     }
+    // called by the histogram kernel, or by the scatter when there is no histogram launch
     __device__ void note(int64_t i, uint32_t d) const {
         if (out_shard) out_shard[i] = (int32_t) d;
     }
@@ -64,11 +71,23 @@ static_assert(PART_HIST_BYTES % 256 == 0, "the totals start 256-byte aligned");
 
 static px_status partition_common(px_ctx* ctx, const int64_t* ids, const int64_t* num_ids, int64_t cap,
                                   int num_shards, px_hash hash, int32_t* out_shard, int32_t* out_perm,
-                                  int64_t* out_offsets, void* work, hipStream_t stream) {
+                                  int64_t* out_offsets, void* work, bool single_launch, hipStream_t stream) {
     uint32_t* hist = (uint32_t*) work;
     uint32_t* totals = (uint32_t*) ((char*) work + PART_HIST_BYTES);
     const px_sort_geom g = px_sort_geometry(cap);
-    ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard, out_offsets};
+    ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard, out_offsets,
+                  nullptr, 0u, ctx->d_flags};
+    // One launch when every block holds a single tile and all the blocks' shard counts together are
+    // few words: the blocks count for themselves and read one another's counts from the context's
+    // words (numbered by call, never cleared).
+    if (single_launch && g.chunk == PX_SORT_TILE && (int64_t) g.n_blocks * num_shards <= PX_PART_PUB_WORDS) {
+        if (++ctx->part_call == 0u) ctx->part_call = 1u;           // 0 is what the words start with
+        pol.pub_words = ctx->d_part_pub;
+        pol.call_no = ctx->part_call;
+        pxr::k_radix_scatter<ShardPass, 8, true><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, totals, g.chunk,
+                                                                                            g.n_blocks, num_shards);
+        return px_check_hip(ctx, hipGetLastError(), "partition launch");
+    }
     pxr::k_radix_hist<ShardPass, 8><<<g.n_blocks, PX_SORT_THREADS, 0, stream>>>(pol, hist, g.chunk);
     // Only the first num_shards bins are ever used.  While a thread of the scatter has at most
     // PX_PART_OWN_ROWS histogram rows to add up for its share of a column, every scatter block adds
@@ -110,7 +129,7 @@ extern "C" px_status px_partition_rows(px_ctx* ctx, const int64_t* ids, const in
     if (((uintptr_t) work) % 256) return px_fail(ctx, PX_ERR_INVALID_ARG, "scratch needs 256-byte alignment");
     const size_t need = px_partition_scratch_bytes(cap);
     if (work_bytes < need) return px_fail(ctx, PX_ERR_SCRATCH_TOO_SMALL, "scratch %zu < %zu bytes", work_bytes, need);
-    return partition_common(ctx, ids, num_ids, cap, num_shards, hash, out_shard, out_perm, out_offsets, work,
+    return partition_common(ctx, ids, num_ids, cap, num_shards, hash, out_shard, out_perm, out_offsets, work, true,
                             (hipStream_t) hip_stream);
 }
 
@@ -157,6 +176,7 @@ extern "C" px_status px_partition_rows_noalloc(px_ctx* ctx, const int64_t* ids, 
                        "use px_partition_rows with a workspace", (long long) cap, (long long) PX_PARTITION_NOALLOC_MAX_IDS);
     if (!ctx->part_scratch)
         return px_fail(ctx, PX_ERR_DEVICE, "the built-in scratch was not found on GPU %d when the context was created", ctx->device);
+    // always the two-launch path on the built-in array: this entry point exists to exercise it
     return partition_common(ctx, ids, num_ids, cap, num_shards, hash, out_shard, out_perm, out_offsets,
-                            ctx->part_scratch, (hipStream_t) hip_stream);
+                            ctx->part_scratch, false, (hipStream_t) hip_stream);
 }

@@ -129,7 +129,19 @@ static __global__ __launch_bounds__(256) void k_radix_prefix(uint32_t* __restric
 // live_bins > 0 (only with own_prefix_blocks > 0): no digit reaches live_bins, and the columns of
 // the live bins are added up by all threads together (256 / live_bins threads per column), so
 // that a pass with few bins can skip the prefix launch at any number of blocks.
-template <class P, int BITS>
+//
+// SELF (needs live_bins > 0, own_prefix_blocks = the grid, and a chunk of one tile): there is no
+// histogram launch either.  Every block counts its own tile, publishes the live bins' counts in
+// p.pub() as 64-bit words (call number << 32 | count), and reads the words of all blocks, waiting
+// for those that do not carry this call's number yet.  The call number makes clearing unnecessary:
+// the words live in memory that starts at zero and only ever holds numbers of earlier calls.  The
+// words are written and read with device-scope atomic accesses.  All blocks of the (small) grid are
+// resident together, so the wait ends as soon as the last one has counted; it is bounded all the
+// same, and a block that gives up calls p.fail() and goes on with what it has (in bounds, wrong).
+#ifndef PX_SELF_SPIN_LIMIT
+#define PX_SELF_SPIN_LIMIT (1 << 18)
+#endif
+template <class P, int BITS, bool SELF = false>
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const uint32_t* __restrict__ hist,
                                                                    const uint32_t* __restrict__ totals,
                                                                    int64_t chunk, int own_prefix_blocks,
@@ -183,8 +195,44 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
                 s_gdst[b] = 0u;
             }
             __syncthreads();
+            if constexpr (SELF) {
+                // own counts (in s_wcnt[0], which the tile loop clears again), published, then everyone's
+                for (int b = tid; b < live_bins; b += PX_SORT_THREADS) s_wcnt[0][b] = 0u;
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < PX_SORT_ITEMS; ++i) {
+                    const int local = wave * (64 * PX_SORT_ITEMS) + i * 64 + (int) lane;
+                    if ((int64_t) local < end - begin) {
+                        atomicAdd(&s_wcnt[0][dg[i]], 1u);
+                        p.note(begin + local, dg[i]);
+                    }
+                }
+                __syncthreads();
+                unsigned long long* pub = p.pub();
+                const unsigned long long tag = (unsigned long long) p.call_number() << 32;
+                for (int b = tid; b < live_bins; b += PX_SORT_THREADS)
+                    __hip_atomic_store(&pub[(size_t) blockIdx.x * live_bins + b], tag | s_wcnt[0][b], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                const int words = own_prefix_blocks * live_bins;
+                for (int i = tid; i < words; i += PX_SORT_THREADS) {
+                    const int b = i / live_bins, bin = i - b * live_bins;
+                    unsigned long long v = __hip_atomic_load(&pub[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int spin = 0; (v >> 32) != (tag >> 32) && spin < PX_SELF_SPIN_LIMIT; ++spin) {
+                        __builtin_amdgcn_s_sleep(2);
+                        v = __hip_atomic_load(&pub[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    if ((v >> 32) != (tag >> 32)) {
+                        p.fail();
+                        v = 0ull;
+                    }
+                    const uint32_t c = (uint32_t) v;
+                    atomicAdd(&s_binstart[bin], c);
+                    if (b < (int) blockIdx.x) atomicAdd(&s_gdst[bin], c);
+                }
+                __syncthreads();
+            }
             const int per_bin = PX_SORT_THREADS / live_bins;           // threads per column (live_bins <= 256)
-            if (tid < per_bin * live_bins) {
+            if (!SELF && tid < per_bin * live_bins) {
                 const int bin = tid % live_bins, slot = tid / live_bins;
                 uint32_t tot = 0u, bef = 0u;
 #pragma unroll 8
