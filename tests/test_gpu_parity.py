@@ -691,6 +691,37 @@ def test_partition_shard_counts(gpu, n_shards, hash_name):
     assert bool((shard[ids.size:] == -1).all()) and bool((perm[ids.size:] == -1).all())
 
 
+@pytest.mark.parametrize("cap,n_shards", [(2047, 3), (2048, 256), (2049, 8), (60_000, 8), (60_000, 64), (60_000, 70),
+                                          (131_072, 32), (131_072, 33), (400_000, 10), (400_000, 11), (1_100_000, 1),
+                                          (1_100_000, 16)])
+def test_partition_one_launch_and_two_launch_paths(gpu, cap, n_shards):
+    """A partition of few blocks x shards runs as one launch whose blocks exchange their shard counts,
+    a larger one as histogram (, prefix) and scatter launches: both sides of every switch, several
+    calls in a row on one context (the exchanged counts are told apart by the call's number), a count
+    well below the capacity, a full one and an empty one."""
+    ctx, px, runner = gpu
+    rng = np.random.default_rng(cap + n_shards)
+    scratch = px.alloc_scratch(px.Context.px_partition_scratch_bytes(cap))
+    d_ids = torch.empty(cap, dtype=torch.int64, device="cuda")
+    for n in (cap, max(1, cap // 3), 0, min(cap, 5)):
+        ids = np.unique(rng.integers(0, 1 << 40, size=n, dtype=np.int64))[:n]
+        hash_name = "mul" if n % 2 else "mod"
+        d_ids.fill_(-999)
+        d_ids[:ids.size] = torch.from_numpy(ids).cuda()
+        num = torch.tensor([ids.size], dtype=torch.int64, device="cuda")
+        shard = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+        perm = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+        off = torch.full((n_shards + 1,), -1, dtype=torch.int64, device="cuda")
+        ctx.px_partition_rows(d_ids, num, cap, n_shards, px.PX_HASH_MUL if hash_name == "mul" else px.PX_HASH_MOD,
+                              shard, perm, off, scratch)
+        o_shard, o_perm, o_off = oracle.partition_rows(ids, n_shards, hash_name)
+        assert np.array_equal(off.cpu().numpy(), o_off)
+        assert np.array_equal(shard[:ids.size].cpu().numpy(), o_shard)
+        assert np.array_equal(perm[:ids.size].cpu().numpy(), o_perm)
+        assert bool((shard[ids.size:] == -1).all()) and bool((perm[ids.size:] == -1).all())
+    assert ctx.px_device_status() == px.PX_OK
+
+
 def test_apply_shard_by_shard_equals_apply_all(gpu):
     ctx, px, runner = gpu
     w = inputs.shrink(inputs.LARGE_LM, vocab=20_000, n_workers=8, n_per_worker=1000, dim=64)
