@@ -80,7 +80,15 @@ static px_status partition_common(px_ctx* ctx, const int64_t* ids, const int64_t
     // One launch when every block holds a single tile and all the blocks' shard counts together are
     // few words: the blocks count for themselves and read one another's counts from the context's
     // words (numbered by call, never cleared).
-    if (single_launch && g.chunk == PX_SORT_TILE && (int64_t) g.n_blocks * num_shards <= PX_PART_PUB_WORDS) {
+    // Not while the stream is being captured: a replayed graph would carry the same call number
+    // again and again, and a block could take the counts of the replay before for this one's.
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (single_launch && stream != nullptr && hipStreamIsCapturing(stream, &capture) != hipSuccess) {
+        (void) hipGetLastError();
+        capture = hipStreamCaptureStatusActive;                    // cannot tell: take the path that is always safe
+    }
+    if (single_launch && capture == hipStreamCaptureStatusNone && g.chunk == PX_SORT_TILE &&
+        (int64_t) g.n_blocks * num_shards <= PX_PART_PUB_WORDS) {
         if (++ctx->part_call == 0u) ctx->part_call = 1u;           // 0 is what the words start with
         pol.pub_words = ctx->d_part_pub;
         pol.call_no = ctx->part_call;

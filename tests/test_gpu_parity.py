@@ -652,17 +652,35 @@ def test_whole_path_replays_from_a_hip_graph(gpu):
             all_ids.copy_(torch.cat(d_idx))
         graph.replay()
         torch.cuda.synchronize()
-        got = (table.clone(), accum.clone(), dense_out.clone(), pulled.clone(), b.out_ids.clone(), int(b.out_num.item()))
+        got = (table.clone(), accum.clone(), dense_out.clone(), pulled.clone(), b.out_ids.clone(), int(b.out_num.item()),
+               b.perm.clone(), b.offsets.clone(), b.shard.clone())
         whole_path(f_table, f_accum)                               # the same step, eagerly, on the twin state
         torch.cuda.synchronize()
         assert ctx.px_device_status() == px.PX_OK
         u = int(b.out_num.item())
         assert got[5] == u and torch.equal(got[4][:u], b.out_ids[:u])
+        assert torch.equal(got[6][:u], b.perm[:u]) and torch.equal(got[7], b.offsets) and torch.equal(got[8][:u], b.shard[:u])
         assert torch.equal(got[0], f_table) and torch.equal(got[1], f_accum)
         assert torch.equal(got[2], dense_out) and torch.equal(got[3], pulled)
     ref_ids, _, _ = oracle.sparse_coalesce(idx, val, w.dim, w.vocab)
     assert np.array_equal(b.out_ids[:u].cpu().numpy(), ref_ids)
     assert not torch.equal(f_table, table0)
+    # three replays in a row, new ids before each, nothing eager in between: whatever a replay leaves
+    # behind in scratch or in the context must not leak into the next one
+    for _ in range(3):
+        idx, val, dense = fresh()
+        for dst, src in zip(d_idx, idx):
+            dst.copy_(torch.from_numpy(src))
+        graph.replay()
+    torch.cuda.synchronize()
+    assert ctx.px_device_status() == px.PX_OK
+    ref_ids, _, ref_len = oracle.sparse_coalesce(idx, [np.zeros((w.n_per_worker, w.dim), np.float32)] * w.n_workers, w.dim, w.vocab)
+    u = int(b.out_num.item())
+    assert u == ref_ids.size and np.array_equal(b.out_ids[:u].cpu().numpy(), ref_ids)
+    assert np.array_equal(b.out_run_len[:u].cpu().numpy(), ref_len)
+    o_shard, o_perm, o_off = oracle.partition_rows(ref_ids, w.n_shards, "mul")
+    assert np.array_equal(b.shard[:u].cpu().numpy(), o_shard) and np.array_equal(b.perm[:u].cpu().numpy(), o_perm)
+    assert np.array_equal(b.offsets.cpu().numpy(), o_off)
 
 
 # ---------------------------------------------------------------- partition
