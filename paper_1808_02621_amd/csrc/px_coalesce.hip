@@ -1003,10 +1003,10 @@ __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
             fixup_finish(a, rec.x, col, acc);
         }
     }
-    if (a.out_run_len != nullptr && blockIdx.y == 0) {
+    if (a.out_run_len != nullptr) {                               // every workgroup of the grid takes its share
         const int64_t n = a.num_unique[0];
-        const int64_t stride = (int64_t) gridDim.x * blockDim.x;
-        for (int64_t u = (int64_t) blockIdx.x * blockDim.x + threadIdx.x; u < n; u += stride)
+        const int64_t stride = (int64_t) gridDim.x * gridDim.y * blockDim.x;
+        for (int64_t u = ((int64_t) blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; u < n; u += stride)
             a.out_run_len[u] = (int32_t) (a.run_start[u + 1] - a.run_start[u]);
     }
 }
