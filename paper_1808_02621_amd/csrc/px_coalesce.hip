@@ -41,7 +41,7 @@ namespace {
 #define PX_TILE_TARGET 8192     // grow the window until there are at most this many tiles
 #endif
 #ifndef PX_WIDE_DIGIT_BLOCKS
-#define PX_WIDE_DIGIT_BLOCKS 128   // sorts of up to this many blocks (256K rows) use digits of up to 11 bits
+#define PX_WIDE_DIGIT_BLOCKS 256   // sorts of up to this many blocks (256K rows) use digits of up to 11 bits
 #endif
 #ifndef PX_ALIGN_DIV
 #define PX_ALIGN_DIV 4          // a tile moves to a head only within the first 1/PX_ALIGN_DIV of its window

@@ -47,11 +47,17 @@ static inline size_t px_align_up(size_t x, size_t a) { return (x + a - 1) / a * 
 
 // ---------------------------------------------------------------- radix passes
 // One stable 8-bit counting pass = histogram per block, prefix over blocks, scatter.
+#ifndef PX_SORT_MAX_BLOCKS_
+#define PX_SORT_MAX_BLOCKS_ 512
+#endif
+#ifndef PX_SORT_ITEMS_PER_THREAD
+#define PX_SORT_ITEMS_PER_THREAD 4     // 1,024-item tiles: the passes are chains of dependent steps, and short tiles make short chains
+#endif
 enum {
     PX_SORT_THREADS = 256,
-    PX_SORT_ITEMS = 8,
+    PX_SORT_ITEMS = PX_SORT_ITEMS_PER_THREAD,
     PX_SORT_TILE = PX_SORT_THREADS * PX_SORT_ITEMS,   // items ranked at once in LDS
-    PX_SORT_MAX_BLOCKS = 512,     // multiple of 64
+    PX_SORT_MAX_BLOCKS = PX_SORT_MAX_BLOCKS_,     // multiple of 64
     PX_RADIX_MAX_BITS = 11,       // widest digit of a counting pass
     PX_RADIX_MAX = 1 << PX_RADIX_MAX_BITS
 };

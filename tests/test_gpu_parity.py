@@ -264,7 +264,7 @@ def test_run_lengths_around_batch_and_window_borders(gpu, dim, bf16):
     assert u == len(lengths)
 
 
-@pytest.mark.parametrize("rows", [65_536, 65_537, 2048 * 33, 2048 * 40 + 1])
+@pytest.mark.parametrize("rows", [32_768, 32_769, 1024 * 33, 65_536, 65_537, 2048 * 33, 2048 * 40 + 1, 262_144, 262_145])
 def test_row_counts_around_the_one_launch_prefix_limit(gpu, rows):
     """Up to 32 sort blocks the scatter sums the histogram rows itself; above, the prefix kernel runs."""
     rng = np.random.default_rng(rows)
@@ -709,7 +709,7 @@ def test_partition_shard_counts(gpu, n_shards, hash_name):
     assert bool((shard[ids.size:] == -1).all()) and bool((perm[ids.size:] == -1).all())
 
 
-@pytest.mark.parametrize("cap,n_shards", [(2047, 3), (2048, 256), (2049, 8), (60_000, 8), (60_000, 64), (60_000, 70),
+@pytest.mark.parametrize("cap,n_shards", [(1023, 5), (1024, 256), (1025, 2), (2047, 3), (2048, 256), (2049, 8), (524_288, 4), (524_289, 4), (60_000, 8), (60_000, 64), (60_000, 70),
                                           (131_072, 32), (131_072, 33), (400_000, 10), (400_000, 11), (1_100_000, 1),
                                           (1_100_000, 16)])
 def test_partition_one_launch_and_two_launch_paths(gpu, cap, n_shards):
