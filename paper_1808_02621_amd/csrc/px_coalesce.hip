@@ -40,6 +40,9 @@ namespace {
 #ifndef PX_TILE_TARGET
 #define PX_TILE_TARGET 8192     // grow the window until there are at most this many tiles
 #endif
+#ifndef PX_TILE_TARGET_FUSED
+#define PX_TILE_TARGET_FUSED 16384   // the fused modes do more per finished run: they like shorter tiles on long inputs
+#endif
 #ifndef PX_WIDE_DIGIT_BLOCKS
 #define PX_WIDE_DIGIT_BLOCKS 256   // sorts of up to this many blocks (256K rows) use digits of up to 11 bits
 #endif
@@ -52,11 +55,13 @@ static_assert(PX_TILE_MIN >= 32 && (PX_TILE_MIN & (PX_TILE_MIN - 1)) == 0 && PX_
 
 // Rows per segsum window (a power of two that divides PX_SORT_TILE): enough tiles to fill the
 // chip, few enough partial rows.
-inline int tile_rows_for(int64_t m) {
+inline int tile_rows_for(int64_t m, bool fused) {
+    const int64_t target = fused ? PX_TILE_TARGET_FUSED : PX_TILE_TARGET;
     int t = PX_TILE_MIN;
-    while (t < PX_TILE_MAX && (int64_t) t * PX_TILE_TARGET < m) t <<= 1;
+    while (t < PX_TILE_MAX && (int64_t) t * target < m) t <<= 1;
     return t;
 }
+static_assert(PX_TILE_TARGET_FUSED >= PX_TILE_TARGET, "scratch is carved for the fused modes' (shorter) tiles");
 
 // How a row of `dim` elements is spread over a lane group: G lanes, C pieces per lane, E elements
 // per piece; rows wider than G*C pieces take several slabs (grid.y).
@@ -117,7 +122,7 @@ struct Scratch {
 
 inline Scratch carve(void* base, int64_t m, int64_t dim) {
     Scratch s;
-    const int t = tile_rows_for(m);
+    const int t = tile_rows_for(m, true);                          // the shorter of the two: at least as many tiles
     const size_t n_tiles = (size_t) ((m + t - 1) / t);
     const size_t n_hblocks = (size_t) ((m + PX_SORT_TILE - 1) / PX_SORT_TILE);
     const size_t pstride = (size_t) max_partial_stride(dim);
@@ -1180,7 +1185,7 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
     uint64_t* dst = other_words;
     const uint64_t* sorted = sorted_words;
 
-    const int tile_rows = tile_rows_for(m);
+    const int tile_rows = tile_rows_for(m, mode != MODE_ROWS);
     const int64_t n_tiles = (m + tile_rows - 1) / tile_rows;
     const int n_hblocks = (int) ((m + PX_SORT_TILE - 1) / PX_SORT_TILE);
     uint64_t* rowref = dst;               // the sort's other buffer is free now
