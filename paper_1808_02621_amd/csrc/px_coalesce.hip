@@ -50,8 +50,8 @@ namespace {
 #define PX_ALIGN_DIV 4          // a tile moves to a head only within the first 1/PX_ALIGN_DIV of its window
 #endif
 
-static_assert(PX_TILE_MIN >= 32 && (PX_TILE_MIN & (PX_TILE_MIN - 1)) == 0 && PX_TILE_MAX <= PX_SORT_TILE,
-              "segsum windows are powers of two between 32 rows and one sort tile");
+static_assert(PX_TILE_MIN >= 8 && (PX_TILE_MIN & (PX_TILE_MIN - 1)) == 0 && PX_TILE_MAX <= PX_SORT_TILE && PX_SORT_TILE / PX_TILE_MIN <= 256,
+              "segsum windows are powers of two between 8 rows and one sort tile, at most 256 of them per sort tile");
 
 // Rows per segsum window (a power of two that divides PX_SORT_TILE): enough tiles to fill the
 // chip, few enough partial rows.
@@ -286,11 +286,11 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
                                                     int64_t* __restrict__ out_num_unique,
                                                     uint32_t* __restrict__ flags) {
     __shared__ uint32_t s_wave[4];
-    __shared__ uint32_t s_first[PX_SORT_TILE / 32];        // first aligning head of each window of this block
-    __shared__ uint32_t s_head[PX_SORT_TILE / 32];         // first head of the window, 0xffffffff if it has none
+    __shared__ uint32_t s_first[PX_SORT_TILE / PX_TILE_MIN];        // first aligning head of each window of this block
+    __shared__ uint32_t s_head[PX_SORT_TILE / PX_TILE_MIN];         // first head of the window, 0xffffffff if it has none
     __shared__ uint64_t s_vbase[PX_MAX_SOURCES];           // the workers' value buffers
     const int tid = threadIdx.x;
-    if (tid < PX_SORT_TILE / 32) {
+    if (tid < PX_SORT_TILE / PX_TILE_MIN) {
         s_first[tid] = 0xffffffffu;
         s_head[tid] = 0xffffffffu;
     }
