@@ -70,7 +70,8 @@ __device__ __forceinline__ void store_state(float* p, float v) { *p = v; }
 
 
 #ifndef PX_APPLY_BLOCKS
-#define PX_APPLY_BLOCKS 4096     // most blocks of one apply launch
+#define PX_APPLY_BLOCKS 16384    // most blocks of one apply launch (65,536 is 4 % faster when every id is distinct and
+                                 // 40 % slower when the capacity is 20 times the number of distinct ids: the grid follows the capacity)
 #endif
 #ifndef PX_APPLY_ROWS
 #define PX_APPLY_ROWS 1         // rows a lane group has in flight when a row is one piece per lane (2 and 4 measured no faster)
