@@ -84,7 +84,10 @@ const char* px_last_error(const px_ctx* ctx);
 
 /* Waits for `hip_stream`, then reports and clears the context's device-side
  * error flag: PX_OK, PX_ERR_INDEX_OUT_OF_RANGE, or PX_ERR_NOT_UNIQUE (in that
- * order of precedence when both were raised).  The only call that blocks. */
+ * order of precedence when both were raised).  PX_ERR_DEVICE, ahead of both,
+ * if a workgroup gave up one of the library's bounded waits for another
+ * workgroup's published count (head ranking, small partitions): the outputs of
+ * that call are then invalid.  The only call that blocks. */
 px_status px_device_status(px_ctx* ctx, void* hip_stream);
 
 /* Bytes of scratch px_sparse_coalesce needs for `total_rows` input rows (over
