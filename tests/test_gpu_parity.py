@@ -60,6 +60,12 @@ def run_chain(gpu, idx, val, dim, vocab, n_shards, hash_name, optimizer, lr, tab
         assert np.array_equal(g_rows, o_rows)
     else:
         close(g_rows, o_rows, rel)
+        # what the double accumulators actually deliver: both sides round the same real sum (formed in
+        # double) once, so they are at most one unit in the last place apart; two when the sum is also
+        # scaled, since the library multiplies by the float scale where the oracle divides by N
+        ulp = np.spacing(np.maximum(np.abs(o_rows), np.float32(1e-30)))
+        worst = float(np.max(np.abs(g_rows.astype(np.float64) - o_rows.astype(np.float64)) / ulp)) if o_rows.size else 0.0
+        assert worst <= (1.0 if scale == 1.0 else 2.0), "aggregated rows up to %.1f ulp from the oracle" % worst
 
     o_shard, o_perm, o_off = oracle.partition_rows(o_ids, n_shards, hash_name)
     assert np.array_equal(b.shard[:u].cpu().numpy(), o_shard)
