@@ -270,9 +270,11 @@ def test_run_lengths_around_batch_and_window_borders(gpu, dim, bf16):
     assert u == len(lengths)
 
 
-@pytest.mark.parametrize("rows", [32_768, 32_769, 1024 * 33, 65_536, 65_537, 2048 * 33, 2048 * 40 + 1, 262_144, 262_145])
+@pytest.mark.parametrize("rows", [1, 255, 1023, 1024, 1025, 2047, 2048, 2049, 4097, 32_768, 32_769, 1024 * 33, 65_536, 65_537, 2048 * 33, 2048 * 40 + 1, 262_144, 262_145])
 def test_row_counts_around_the_one_launch_prefix_limit(gpu, rows):
-    """Up to 32 sort blocks the scatter sums the histogram rows itself; above, the prefix kernel runs."""
+    """Row counts on both sides of every switch of the sort's geometry: one tile (1,024 rows) and its
+    multiples, 32 sort blocks (up to which the scatter sums the histogram rows itself; above, the
+    prefix kernel runs), 256 blocks (wide digits up to there), and a ragged last tile."""
     rng = np.random.default_rng(rows)
     vocab, dim = 70_000, 4
     sizes = rng.multinomial(rows, np.ones(3) / 3)
