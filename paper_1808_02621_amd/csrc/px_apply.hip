@@ -106,16 +106,24 @@ __global__ __launch_bounds__(256) void k_apply(ApplyArgs p) {
             k[r] = ok[r] ? (p.perm ? (int64_t) p.perm[j0 + r] : j0 + r) : 0;
             ok[r] = ok[r] && k[r] >= 0 && k[r] < n;
         }
+        // the id and its two neighbours' are requested together (positions clamped to the list)
+        int64_t id_before[R], id_after[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            id[r] = ok[r] ? p.ids[k[r]] : 0;
+            const int64_t kk = ok[r] ? k[r] : 0;
+            id[r] = n > 0 ? p.ids[kk] : 0;
+            id_before[r] = n > 0 ? p.ids[kk > 0 ? kk - 1 : 0] : 0;
+            id_after[r] = n > 0 ? p.ids[kk + 1 < n ? kk + 1 : n - 1] : 0;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
             if (ok[r] && (id[r] < 0 || id[r] >= p.vocab)) {
                 if (gl == 0) atomicOr(p.flags, (uint32_t) PXF_BAD_ID);
                 ok[r] = false;
             }
             // An id that repeats its neighbour's (any repeat, when the ids are sorted) would be updated by
             // two lane groups at once: neither touches the row, and the flag is raised.
-            if (ok[r] && ((k[r] > 0 && p.ids[k[r] - 1] == id[r]) || (k[r] + 1 < n && p.ids[k[r] + 1] == id[r]))) {
+            if (ok[r] && ((k[r] > 0 && id_before[r] == id[r]) || (k[r] + 1 < n && id_after[r] == id[r]))) {
                 if (gl == 0) atomicOr(p.flags, (uint32_t) PXF_NOT_UNIQUE);
                 ok[r] = false;
             }
