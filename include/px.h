@@ -90,6 +90,14 @@ const char* px_last_error(const px_ctx* ctx);
  * that call are then invalid.  The only call that blocks. */
 px_status px_device_status(px_ctx* ctx, void* hip_stream);
 
+/* Two kernels let a workgroup wait for a count another workgroup publishes (head ranking in the
+ * coalesce calls; px_partition_rows when it runs as one launch).  Every such wait is bounded: after
+ * `polls` polls (default 2^18, about a third of a second) the workgroup gives up, the call's outputs
+ * are invalid, nothing is read or written out of bounds, later updates on the context leave their
+ * tables alone, and px_device_status reports PX_ERR_DEVICE.  0 makes every wait give up at its first
+ * unsuccessful poll, which is how the error path is tested; 0 <= polls <= 2^30. */
+px_status px_set_wait_limit(px_ctx* ctx, int64_t polls);
+
 /* Bytes of scratch px_sparse_coalesce needs for `total_rows` input rows (over
  * all workers) of width `dim` elements.  Depends on nothing else. */
 size_t px_coalesce_scratch_bytes(int64_t total_rows, int64_t dim);

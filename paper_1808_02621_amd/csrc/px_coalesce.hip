@@ -269,12 +269,10 @@ struct SortWords {
 // publishes its own count in hpub (cleared by the pack kernel) with the top bit as the "valid"
 // mark, then reads the words of all blocks before it, waiting for those not yet valid.  A block
 // only ever waits for blocks with smaller numbers, which the hardware starts no later than it, and
-// those never wait for it; the wait is bounded all the same, and a block that gives up raises
-// PXF_INTERNAL.  The words are written and read with device-scope atomic accesses, which the
+// those never wait for it; the wait is bounded all the same (wait_polls polls), and a block that
+// gives up raises PXF_INTERNAL: its ranks are then too small, which keeps every store of this kernel
+// in bounds, and the kernels that would follow the ranks (segmented sum, fix-up) leave at once.  The words are written and read with device-scope atomic accesses, which the
 // dies' separate L2 caches do not hold back.
-#ifndef PX_HEADS_SPIN_LIMIT
-#define PX_HEADS_SPIN_LIMIT (1 << 18)
-#endif
 __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__ sorted, int64_t m,
                                                     uint32_t* __restrict__ hpub, int tile_rows,
                                                     const uint64_t* __restrict__ words, int n_workers,
@@ -284,7 +282,7 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
                                                     uint32_t* __restrict__ run_start,
                                                     uint4* __restrict__ tile_info,
                                                     int64_t* __restrict__ out_num_unique,
-                                                    uint32_t* __restrict__ flags) {
+                                                    uint32_t* __restrict__ flags, int wait_polls) {
     __shared__ uint32_t s_wave[4];
     __shared__ uint32_t s_first[PX_SORT_TILE / PX_TILE_MIN];        // first aligning head of each window of this block
     __shared__ uint32_t s_head[PX_SORT_TILE / PX_TILE_MIN];         // first head of the window, 0xffffffff if it has none
@@ -345,7 +343,7 @@ __global__ __launch_bounds__(256) void k_heads_emit(const uint64_t* __restrict__
     uint32_t part = 0;
     for (int b = tid; b < (int) blockIdx.x; b += 256) {
         uint32_t v = __hip_atomic_load(&hpub[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (int spin = 0; !(v & 0x80000000u) && spin < PX_HEADS_SPIN_LIMIT; ++spin) {
+        for (int spin = 0; !(v & 0x80000000u) && spin < wait_polls; ++spin) {
             __builtin_amdgcn_s_sleep(2);
             v = __hip_atomic_load(&hpub[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -533,7 +531,9 @@ __global__ __launch_bounds__(256) void k_segsum(SegsumArgs a) {
            SV = VEC ? E / 4 : 1 };                                // state vectors (float4 or float) per piece
     typedef typename std::conditional<VEC, float4, float>::type StateV;
     __shared__ double s_part[MERGE ? TPB * G * C * E : 1];
-    if (FUSED && a.flags[0]) return;                              // uniform: an error flag is up, touch nothing
+    // uniform: the head ranking gave up a wait, so ranks and run starts cannot be trusted (any mode);
+    // or, fused modes, an error flag is up: touch nothing
+    if ((a.flags[0] & PXF_INTERNAL) || (FUSED && a.flags[0])) return;
 
     const int gl = threadIdx.x % G;
     const int gj = threadIdx.x / G;                               // tile inside the block
@@ -925,7 +925,7 @@ __device__ __forceinline__ void fixup_finish(const FixupArgs& a, uint32_t u, int
 
 __global__ __launch_bounds__(64 * FIX_SPLITS) void k_fixup(FixupArgs a) {
     __shared__ double s_red[FIX_SPLITS][64];
-    if (a.mode != MODE_ROWS && a.flags[0]) return;                // uniform: an error flag is up, touch nothing
+    if ((a.flags[0] & PXF_INTERNAL) || (a.mode != MODE_ROWS && a.flags[0])) return;   // uniform, as in the segmented sum
     const int lane = threadIdx.x & 63, split = threadIdx.x >> 6;
     const int64_t pe = (int64_t) blockIdx.y * 64 + lane;          // slot in the partial row
     // which column does slot pe hold?
@@ -1191,7 +1191,7 @@ static px_status coalesce_common(px_ctx* ctx, int mode, int n_workers, const int
     uint64_t* rowref = dst;               // the sort's other buffer is free now
     k_heads_emit<<<n_hblocks, 256, 0, stream>>>(sorted, m, sc.hcount, tile_rows, ctx->d_words, n_workers, local_bits,
                                                 dim * (int64_t) es, rowref, out_ids, sc.run_start, sc.tile_info,
-                                                out_num_unique, ctx->d_flags);
+                                                out_num_unique, ctx->d_flags, ctx->wait_polls);
 
     const RowShape sh = row_shape(dim, (int) es, vec);
     SegsumArgs a;

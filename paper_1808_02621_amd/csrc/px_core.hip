@@ -58,6 +58,7 @@ extern "C" px_status px_create(px_ctx** out, int device) {
     px_ctx* ctx = (px_ctx*) calloc(1, sizeof(px_ctx));
     if (!ctx) return PX_ERR_DEVICE;
     ctx->device = device;
+    ctx->wait_polls = PX_WAIT_POLLS_DEFAULT;
     int prev = 0;
     (void) hipGetDevice(&prev);
     hipError_t e = hipSetDevice(device);
@@ -85,6 +86,13 @@ extern "C" px_status px_destroy(px_ctx* ctx) {
     if (ctx->d_part_pub) (void) hipFree(ctx->d_part_pub);
     if (ctx->h_flags) (void) hipHostFree(ctx->h_flags);
     free(ctx);
+    return PX_OK;
+}
+
+extern "C" px_status px_set_wait_limit(px_ctx* ctx, int64_t polls) {
+    if (!ctx) return PX_ERR_INVALID_ARG;
+    if (polls < 0 || polls > (1ll << 30)) return px_fail(ctx, PX_ERR_INVALID_ARG, "wait limit %lld outside [0, 2^30]", (long long) polls);
+    ctx->wait_polls = (int) polls;
     return PX_OK;
 }
 

@@ -16,12 +16,15 @@ struct px_ctx {
     void* part_scratch;  // device address of the partition's built-in scratch on this GPU (not owned)
     unsigned long long* d_part_pub;   // device: PX_PART_PUB_WORDS words, shard counts published by a single-launch partition
     uint32_t part_call;  // number of the last single-launch partition on this context (tags the published words)
+    int wait_polls;      // polls before a workgroup gives up a bounded wait (px_set_wait_limit)
     char err[512];
 };
 
 // d_words holds, per call, [idx pointers | value pointers | row prefix (n + 1)] for coalesce
 // and [buffer pointers] for the dense mean.
 enum { PXW_TOTAL = 3 * PX_MAX_SOURCES + 8 };
+
+enum { PX_WAIT_POLLS_DEFAULT = 1 << 18 };   // about a third of a second of polling
 
 enum { PX_PART_PUB_WORDS = 2048 };   // most (blocks x shards) of a single-launch partition: 8 words per thread to read
 

@@ -26,6 +26,7 @@ struct ShardPass {
     unsigned long long* pub_words;         // single-launch mode: the blocks' published shard counts
     uint32_t call_no;                      //   and the number of this call
     uint32_t* flags;                       //   the context's error flags
+    int polls;                             //   polls before a block gives up waiting for another's counts
 
     __device__ int64_t count() const {
         int64_t n = num[0];
@@ -36,6 +37,7 @@ struct ShardPass {
     __device__ unsigned long long* pub() const { return pub_words; }
     __device__ uint32_t call_number() const { return call_no; }
     __device__ void fail() const { atomicOr(flags, (uint32_t) PXF_INTERNAL); }
+    __device__ int wait_polls() const { return polls; }
     __device__ Item load(int64_t i) const { return (uint32_t) i; }
     __device__ uint32_t digit(Item, int64_t i) const {
         uint64_t h = (uint64_t) ids[i];
@@ -76,7 +78,7 @@ static px_status partition_common(px_ctx* ctx, const int64_t* ids, const int64_t
     uint32_t* totals = (uint32_t*) ((char*) work + PART_HIST_BYTES);
     const px_sort_geom g = px_sort_geometry(cap);
     ShardPass pol{ids, num_ids, cap, (uint32_t) num_shards, hash == PX_HASH_MUL ? 1 : 0, out_perm, out_shard, out_offsets,
-                  nullptr, 0u, ctx->d_flags};
+                  nullptr, 0u, ctx->d_flags, ctx->wait_polls};
     // One launch when every block holds a single tile and all the blocks' shard counts together are
     // few words: the blocks count for themselves and read one another's counts from the context's
     // words (numbered by call, never cleared).

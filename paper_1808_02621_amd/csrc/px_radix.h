@@ -138,9 +138,6 @@ static __global__ __launch_bounds__(256) void k_radix_prefix(uint32_t* __restric
 // words are written and read with device-scope atomic accesses.  All blocks of the (small) grid are
 // resident together, so the wait ends as soon as the last one has counted; it is bounded all the
 // same, and a block that gives up calls p.fail() and goes on with what it has (in bounds, wrong).
-#ifndef PX_SELF_SPIN_LIMIT
-#define PX_SELF_SPIN_LIMIT (1 << 18)
-#endif
 template <class P, int BITS, bool SELF = false>
 __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const uint32_t* __restrict__ hist,
                                                                    const uint32_t* __restrict__ totals,
@@ -217,7 +214,7 @@ __global__ __launch_bounds__(PX_SORT_THREADS) void k_radix_scatter(P p, const ui
                 for (int i = tid; i < words; i += PX_SORT_THREADS) {
                     const int b = i / live_bins, bin = i - b * live_bins;
                     unsigned long long v = __hip_atomic_load(&pub[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    for (int spin = 0; (v >> 32) != (tag >> 32) && spin < PX_SELF_SPIN_LIMIT; ++spin) {
+                    for (int spin = 0; (v >> 32) != (tag >> 32) && spin < p.wait_polls(); ++spin) {
                         __builtin_amdgcn_s_sleep(2);
                         v = __hip_atomic_load(&pub[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }

@@ -37,7 +37,7 @@ EXPORTS = [
     "px_partition_rows", "px_sparse_apply_sgd", "px_sparse_apply_adagrad", "px_dense_average",
     "px_sparse_coalesce_apply_sgd", "px_sparse_coalesce_apply_adagrad", "px_sparse_lookup",
     "px_partition_cost_fit", "px_partition_cost_argmin", "px_partition_search_next",
-    "px_dense_average_launches", "px_partition_rows_noalloc",
+    "px_dense_average_launches", "px_partition_rows_noalloc", "px_set_wait_limit",
 ]
 
 if not os.path.exists(LIBRARY):
@@ -62,6 +62,8 @@ lib.px_last_error.restype = ctypes.c_char_p
 lib.px_last_error.argtypes = [_vp]
 lib.px_device_status.restype = _int
 lib.px_device_status.argtypes = [_vp, _vp]
+lib.px_set_wait_limit.restype = _int
+lib.px_set_wait_limit.argtypes = [_vp, _i64]
 lib.px_coalesce_scratch_bytes.restype = _sz
 lib.px_coalesce_scratch_bytes.argtypes = [_i64, _i64]
 lib.px_partition_scratch_bytes.restype = _sz
@@ -161,6 +163,10 @@ class Context:
     def px_device_status(self, stream=None) -> int:
         """Waits for the stream; returns PX_OK, PX_ERR_INDEX_OUT_OF_RANGE or PX_ERR_NOT_UNIQUE and clears the flag."""
         return lib.px_device_status(self._h, _stream(stream))
+
+    def px_set_wait_limit(self, polls: int) -> None:
+        """Polls before a workgroup gives up a bounded wait for another's count (0: at once)."""
+        self._check(lib.px_set_wait_limit(self._h, polls))
 
     @staticmethod
     def px_coalesce_scratch_bytes(total_rows: int, dim: int) -> int:

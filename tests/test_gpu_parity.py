@@ -505,6 +505,52 @@ def test_repeated_id_in_apply_is_reported_and_its_row_left_alone(gpu):
     assert ctx.px_device_status() == px.PX_OK and float(t4.sum()) == -4.0 * dim
 
 
+def test_a_given_up_wait_is_reported_and_harmless(gpu):
+    """The head ranking and the one-launch partition let a workgroup wait, for a bounded number of
+    polls, for counts other workgroups publish.  With the limit at 0 every wait that is not already
+    satisfied is given up: the call must still end normally, touch nothing out of bounds, leave the
+    table alone and report PX_ERR_DEVICE (or, if no workgroup ever had to wait, give the right
+    result); with the limit restored the same context works again."""
+    _, px, runner = gpu
+    ctx = px.Context(0)
+    with pytest.raises(px.PxError):
+        ctx.px_set_wait_limit(-1)
+    w = inputs.shrink(inputs.LARGE_LM, vocab=50_000, n_per_worker=2_000, dim=64)     # 96,000 rows: 94 sort blocks
+    idx, val = inputs.sparse_ids(w), inputs.sparse_values(w)
+    table = inputs.table_init(w)
+    accum = inputs.accum_init(w)
+    d_idx = [runner.to_device(i) for i in idx]
+    d_val = [runner.to_device(v) for v in val]
+    o_ids, o_rows, _ = oracle.sparse_coalesce(idx, val, w.dim, w.vocab)
+    _, o_perm, o_off = oracle.partition_rows(o_ids, w.n_shards, "mul")
+    ref_t, ref_a = table.copy(), accum.copy()
+    oracle.sparse_apply_adagrad(ref_t, ref_a, o_ids, o_rows, w.lr, perm=o_perm)
+    seen = set()
+    for limit in (0, 0, 0, 1 << 18):
+        ctx.px_set_wait_limit(limit)
+        b = runner.sparse_buffers(d_idx, d_val, w.dim, w.vocab, w.n_shards, px.PX_HASH_MUL)
+        d_t, d_a = torch.from_numpy(table).cuda(), torch.from_numpy(accum).cuda()
+        runner.sparse_step(ctx, b, d_t, d_a, "adagrad", w.lr)
+        status = ctx.px_device_status()
+        seen.add(status)
+        assert status in (px.PX_OK, px.PX_ERR_DEVICE)
+        if limit:
+            assert status == px.PX_OK
+        if status == px.PX_ERR_DEVICE:
+            assert np.array_equal(d_t.cpu().numpy(), table) and np.array_equal(d_a.cpu().numpy(), accum)
+            assert 0 <= int(b.out_num.item()) <= o_ids.size
+        else:
+            u = int(b.out_num.item())
+            assert u == o_ids.size and np.array_equal(b.out_ids[:u].cpu().numpy(), o_ids)
+            assert np.array_equal(b.perm[:u].cpu().numpy(), o_perm) and np.array_equal(b.offsets.cpu().numpy(), o_off)
+            close(b.out_rows[:u].cpu().numpy(), o_rows)
+            close(d_t.cpu().numpy()[o_ids], ref_t[o_ids])
+            close(d_a.cpu().numpy()[o_ids], ref_a[o_ids])
+        assert ctx.px_device_status() == px.PX_OK                  # reported once, then cleared
+    assert px.PX_OK in seen
+    ctx.close()
+
+
 def test_host_side_argument_errors(gpu):
     ctx, px, runner = gpu
     dim, vocab = 16, 100
