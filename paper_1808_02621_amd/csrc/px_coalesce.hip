@@ -17,8 +17,9 @@
 //              double.  Whole runs are rounded and written at once; a split run leaves one
 //              double-precision partial row per tile
 //   5. fixup   each split run adds up its partial rows, rounds once, writes its row
-// Nothing waits on another workgroup and global atomics only append to the list of split
-// runs, so the sums are deterministic.
+// The only wait on another workgroup is the head ranking's (a block reads the head counts of the
+// blocks before it; bounded, see k_heads_emit), and global atomics only append to the list of
+// split runs, so the sums are deterministic.
 #include <string.h>
 
 #include <type_traits>

@@ -6,7 +6,8 @@
 // with the shard number as the digit, so ascending ids stay ascending inside a
 // shard; the scan of the per-shard totals is the offsets array.  The number of
 // ids is a device scalar: the grid is sized for the capacity and every block
-// clamps to the real count.
+// clamps to the real count.  Small partitions run as a single launch (the blocks
+// exchange their shard counts), larger ones as histogram and scatter launches.
 #include <mutex>
 
 #include "px_radix.h"

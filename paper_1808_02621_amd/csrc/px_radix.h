@@ -1,15 +1,18 @@
 // Stable counting pass (8- to 11-bit digits) for wave64: the building block of the id sort
 // (least-significant-digit radix sort) and of the shard partition.
 //
-// A pass is three kernels and uses no atomics on global memory and no waiting
-// between workgroups:
+// A pass is up to three kernels; in that form it uses no atomics on global memory and no
+// waiting between workgroups:
 //   hist     block b counts the digits of its chunk        -> hist[b][bins]
 //   prefix   one wave per digit turns its column of hist into an exclusive prefix
 //            over the blocks and writes the digit's total  -> hist[b][bins], totals[bins]
 //   scatter  block b scans the totals, adds its own prefix row, then ranks its
 //            chunk tile by tile in LDS and writes every item to its final place.
 // With at most PX_OWN_PREFIX_BLOCKS blocks the prefix kernel is skipped: every scatter block
-// adds up the (few) raw histogram rows itself, which costs less than a launch.
+// adds up the (few) raw histogram rows itself, which costs less than a launch.  A pass whose
+// digit takes only a few values (the shard partition) skips it at any size, and, while
+// blocks x values is small, the histogram kernel too: the scatter blocks then count for
+// themselves and read one another's counts (see k_radix_scatter).
 // Ranking inside a tile is by wave-wide digit matching (ballots), with one LDS
 // counter row per wave, so equal digits keep their input order.
 #ifndef PX_RADIX_H_
