@@ -47,7 +47,7 @@ def test_dense_bytes_of_the_headline_call():
 
 
 def test_measured_statistics_of_the_recipe():
-    """Distinct ids per workload, as quoted in the design notes (seeded, so exact)."""
+    """Distinct ids per workload: the recipe is seeded, so the counts are exact and any change to it shows here."""
     assert _unique(inputs.TINY) == 526
     assert _unique(inputs.SMALL_LM) == 5_456
     assert _unique(inputs.LARGE_LM) == 42_915
