@@ -3,8 +3,8 @@
 // Parallax Sec. 2.1: AllReduce computes the sum over the workers of their
 // gradients (Sec. 4.1: or the average); this is the reduction one GPU performs
 // on the slice it owns.  One streaming pass: each thread owns four 16-byte pieces of
-// every input buffer (4 floats or 8 bfloat16 each), reads them from two buffers at a
-// time, adds in worker order and writes once.  Pure HBM streaming: N*C*es bytes in, C*4 (or C*2) out.
+// every input buffer (4 floats or 8 bfloat16 each), reads them buffer by buffer,
+// adds in worker order and writes once.  Pure HBM streaming: N*C*es bytes in, C*4 (or C*2) out.
 #include <string.h>
 
 #include "px_internal.h"
@@ -18,7 +18,8 @@ typedef double acc_t;
 #endif
 
 #ifndef PX_DENSE_BATCH
-#define PX_DENSE_BATCH 2        // buffers a thread reads from at a time (with 4 pieces each: 8 loads in flight)
+#define PX_DENSE_BATCH 1        // buffers a thread reads from at a time (with 4 pieces each: 4 loads in flight; two
+                                // buffers at a time, 8 loads, are 2-3 % slower on 48 bfloat16 buffers and the same elsewhere)
 #endif
 enum { DENSE_BATCH = PX_DENSE_BATCH };
 #ifndef PX_DENSE_PIECES
