@@ -72,6 +72,9 @@ template <> struct In<uint16_t> {
     static __device__ __forceinline__ float widen(uint16_t v) { return __uint_as_float((uint32_t) v << 16); }
 };
 
+#ifndef PX_DENSE_THREADS
+#define PX_DENSE_THREADS 256    // threads of a k_dense_vec workgroup
+#endif
 // A workgroup owns 4 consecutive kilobyte-rows of 256 pieces (16 bytes each) of every buffer; a thread
 // owns one piece of each row.
 #ifndef PX_DENSE_LAUNCH_PIECES
@@ -85,7 +88,7 @@ template <> struct In<uint16_t> {
 // buffers, inside the launch arguments (pack, CARRIED), which saves the upload launch.
 // One launch covers pieces [first, pieces).
 template <typename TIN, bool OUT_BF16, bool CARRIED>
-__global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ words, px_word_pack pack,
+__global__ __launch_bounds__(PX_DENSE_THREADS) void k_dense_vec(const uint64_t* __restrict__ words, px_word_pack pack,
                                                    int n_buffers, int64_t first, int64_t pieces,
                                                    void* __restrict__ out, float scale) {
     enum { E = In<TIN>::E };
@@ -100,7 +103,7 @@ __global__ __launch_bounds__(256) void k_dense_vec(const uint64_t* __restrict__ 
     bool okp[P];
 #pragma unroll
     for (int q = 0; q < P; ++q) {
-        ip[q] = first + ((int64_t) lb * P + q) * 256 + threadIdx.x;
+        ip[q] = first + ((int64_t) lb * P + q) * PX_DENSE_THREADS + threadIdx.x;
         okp[q] = ip[q] < pieces;
         if (!okp[q]) ip[q] = pieces - 1;
     }
@@ -197,7 +200,7 @@ void launch(px_ctx* ctx, const px_word_pack& pack, int n, int64_t count, bool ve
         const int64_t per_launch = pieces_per_launch(n, E * (OUT_BF16 ? 2 : 4));
         for (int64_t first = 0; first < pieces; first += per_launch) {
             const int64_t last = first + per_launch < pieces ? first + per_launch : pieces;
-            k_dense_vec<TIN, OUT_BF16, CARRIED><<<px_round_up_8((unsigned) ((last - first + 256 * PX_DENSE_PIECES - 1) / (256 * PX_DENSE_PIECES))), 256, 0, stream>>>(
+            k_dense_vec<TIN, OUT_BF16, CARRIED><<<px_round_up_8((unsigned) ((last - first + PX_DENSE_THREADS * PX_DENSE_PIECES - 1) / (PX_DENSE_THREADS * PX_DENSE_PIECES))), PX_DENSE_THREADS, 0, stream>>>(
                 ctx->d_words, pack, n, first, last, out, scale);
         }
         done = pieces * E;
