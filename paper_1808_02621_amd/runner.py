@@ -80,12 +80,13 @@ def apply(ctx: px.Context, b: SparseBuffers, table: torch.Tensor, accum: Optiona
           optimizer: str, lr: float, eps: float = 0.0, use_perm: bool = True,
           range_: Optional[torch.Tensor] = None, stream=None) -> None:
     perm = b.perm if use_perm else None
+    # as for the partition: no more distinct ids than input rows, nor than rows in the table
+    cap = max(1, min(b.total_rows, b.vocab))
     if optimizer == "sgd":
-        ctx.px_sparse_apply_sgd(table, b.out_ids, b.out_rows, b.out_num, b.total_rows, perm, range_, lr,
-                                stream)
+        ctx.px_sparse_apply_sgd(table, b.out_ids, b.out_rows, b.out_num, cap, perm, range_, lr, stream)
     elif optimizer == "adagrad":
-        ctx.px_sparse_apply_adagrad(table, accum, b.out_ids, b.out_rows, b.out_num, b.total_rows, perm,
-                                    range_, lr, eps, stream)
+        ctx.px_sparse_apply_adagrad(table, accum, b.out_ids, b.out_rows, b.out_num, cap, perm, range_, lr, eps,
+                                    stream)
     else:
         raise ValueError(optimizer)
 
